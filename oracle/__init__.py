@@ -1,0 +1,223 @@
+"""ctypes front end of the CPU oracle (``sr_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``, by the smoke check and by
+the benchmark's ``cpu_baseline`` leg.  It never imports the product package
+and the product package never imports it.
+
+Arrays are numpy; bf16 tensors travel as ``uint16`` bit patterns.  The oracle
+returns fp64 results.  See the header of ``sr_oracle.c`` for what is computed
+and which passage of the paper (Sections 3, 4.2, 4.3, Appendix A) each part
+follows.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass, field
+from typing import Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "sr_oracle.c")
+_LIB = os.path.join(_HERE, "libsr_oracle.so")
+
+
+def build(force: bool = False) -> str:
+    """Compile ``sr_oracle.c`` with gcc (fp64, OpenMP); returns the library path."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared",
+               "-ffp-contract=off", "-fno-fast-math", "-Wall", "-Wextra",
+               _SRC, "-o", tmp, "-lm"]
+        subprocess.run(cmd, check=True)
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+class _Cfg(ctypes.Structure):
+    _fields_ = [
+        ("batch", ctypes.c_int32),
+        ("n_q_heads", ctypes.c_int32),
+        ("n_kv_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32),
+        ("max_seq_len", ctypes.c_int32),
+        ("routing_enabled", ctypes.c_int32),
+        ("want_dense", ctypes.c_int32),
+        ("reserved", ctypes.c_int32),
+        ("sm_scale", ctypes.c_double),
+        ("tau_coef", ctypes.c_double * 4),
+        ("len_norm", ctypes.c_double),
+    ]
+
+
+_lib = None
+
+
+def _load(path: Optional[str] = None):
+    """Load the oracle library (built on demand); ``path`` loads another build of it
+    (the mutation tests compile deliberately broken copies of the source)."""
+    global _lib
+    if path is not None:
+        lib = ctypes.CDLL(path)
+        assert lib.sr_oracle_cfg_size() == ctypes.sizeof(_Cfg)
+        return lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        assert lib.sr_oracle_cfg_size() == ctypes.sizeof(_Cfg)
+        _lib = lib
+    return _lib
+
+
+def threads() -> int:
+    """Number of OpenMP threads the oracle will use."""
+    return int(_load().sr_oracle_threads())
+
+
+@dataclass
+class OracleResult:
+    out: np.ndarray                      # [B,Hq,D] fp64; zeros for Sink Groups
+    mask: np.ndarray                     # [B,Hkv] uint8; 1 = Sink Group
+    head_cos: np.ndarray                 # [B,Hq]  s_{g,i}
+    group_score: np.ndarray              # [B,Hkv] S_g
+    tau: np.ndarray                      # [B]
+    dense_out: Optional[np.ndarray] = None   # [B,Hq,D] attention ignoring routing
+    alpha0: Optional[np.ndarray] = None      # [B,Hq] softmax mass on token 0
+    lse: Optional[np.ndarray] = None         # [B,Hq]
+    extra: dict = field(default_factory=dict)
+
+
+def _u16(a, shape):
+    a = np.ascontiguousarray(a)
+    if a.dtype != np.uint16:
+        raise TypeError("bf16 tensors are passed as uint16 bit patterns")
+    if tuple(a.shape) != tuple(shape):
+        raise ValueError("shape %r, expected %r" % (a.shape, shape))
+    return a
+
+
+def _cfg(B, Hq, Hkv, D, Lmax, routing_enabled, want_dense, sm_scale, tau_coef, len_norm):
+    c = _Cfg()
+    c.batch, c.n_q_heads, c.n_kv_heads, c.head_dim, c.max_seq_len = B, Hq, Hkv, D, Lmax
+    c.routing_enabled = int(bool(routing_enabled))
+    c.want_dense = int(bool(want_dense))
+    c.sm_scale = float(sm_scale)
+    for i in range(4):
+        c.tau_coef[i] = float(tau_coef[i])
+    c.len_norm = float(len_norm)
+    return c
+
+
+def _ptr(a, ty):
+    return a.ctypes.data_as(ctypes.POINTER(ty)) if a is not None else None
+
+
+def decode(q, k_cache, v_cache, seq_lens, *, tau_coef: Sequence[float] = (0.0, 0.0, 0.0, 0.55),
+           len_norm: float = 0.0, sm_scale: float = 0.0, routing_enabled: bool = True,
+           k0_norm=None, want_dense: bool = False, diagnostics: bool = True,
+           libpath: Optional[str] = None) -> OracleResult:
+    """Routed decode attention in fp64 (single pass over each head's scores).
+
+    q [B,Hq,D], k_cache/v_cache [B,Hkv,Lmax,D] as uint16 bf16 bits,
+    seq_lens [B] int32 (valid rows, current token included).
+    """
+    lib = _load(libpath)
+    q = np.ascontiguousarray(q)
+    B, Hq, D = q.shape
+    k_cache = np.ascontiguousarray(k_cache)
+    _, Hkv, Lmax, _ = k_cache.shape
+    q = _u16(q, (B, Hq, D))
+    k_cache = _u16(k_cache, (B, Hkv, Lmax, D))
+    v_cache = _u16(v_cache, (B, Hkv, Lmax, D))
+    sl = np.ascontiguousarray(np.asarray(seq_lens, dtype=np.int32))
+    assert sl.shape == (B,)
+    c = _cfg(B, Hq, Hkv, D, Lmax, routing_enabled, want_dense, sm_scale, tau_coef, len_norm)
+    out = np.empty((B, Hq, D), np.float64)
+    mask = np.empty((B, Hkv), np.uint8)
+    head_cos = np.empty((B, Hq), np.float64)
+    group_score = np.empty((B, Hkv), np.float64)
+    tau = np.empty((B,), np.float64)
+    dense = np.empty((B, Hq, D), np.float64) if diagnostics else None
+    alpha0 = np.empty((B, Hq), np.float64) if diagnostics else None
+    lse = np.empty((B, Hq), np.float64) if diagnostics else None
+    kn = None
+    if k0_norm is not None:
+        kn = np.ascontiguousarray(np.asarray(k0_norm, dtype=np.float64))
+        assert kn.shape == (B, Hkv)
+    dp = ctypes.c_double
+    rc = lib.sr_oracle_decode(
+        _ptr(q, ctypes.c_uint16), _ptr(k_cache, ctypes.c_uint16), _ptr(v_cache, ctypes.c_uint16),
+        _ptr(sl, ctypes.c_int32), _ptr(kn, dp), ctypes.byref(c),
+        _ptr(out, dp), _ptr(mask, ctypes.c_uint8), _ptr(head_cos, dp), _ptr(group_score, dp),
+        _ptr(tau, dp), _ptr(dense, dp), _ptr(alpha0, dp), _ptr(lse, dp))
+    if rc != 0:
+        raise RuntimeError("sr_oracle_decode failed: %d" % rc)
+    return OracleResult(out, mask, head_cos, group_score, tau, dense, alpha0, lse)
+
+
+def route(q, k_cache, seq_lens, *, tau_coef=(0.0, 0.0, 0.0, 0.55), len_norm: float = 0.0,
+          routing_enabled: bool = True, k0_norm=None, libpath: Optional[str] = None) -> OracleResult:
+    """Routing decision only (cosine, group mean, threshold); reads row 0 of k_cache."""
+    lib = _load(libpath)
+    q = np.ascontiguousarray(q)
+    B, Hq, D = q.shape
+    k_cache = np.ascontiguousarray(k_cache)
+    _, Hkv, Lmax, _ = k_cache.shape
+    q = _u16(q, (B, Hq, D))
+    k_cache = _u16(k_cache, (B, Hkv, Lmax, D))
+    sl = np.ascontiguousarray(np.asarray(seq_lens, dtype=np.int32))
+    c = _cfg(B, Hq, Hkv, D, Lmax, routing_enabled, False, 0.0, tau_coef, len_norm)
+    mask = np.empty((B, Hkv), np.uint8)
+    head_cos = np.empty((B, Hq), np.float64)
+    group_score = np.empty((B, Hkv), np.float64)
+    tau = np.empty((B,), np.float64)
+    kn = None
+    if k0_norm is not None:
+        kn = np.ascontiguousarray(np.asarray(k0_norm, dtype=np.float64))
+    dp = ctypes.c_double
+    rc = lib.sr_oracle_route(
+        _ptr(q, ctypes.c_uint16), _ptr(k_cache, ctypes.c_uint16), _ptr(sl, ctypes.c_int32),
+        _ptr(kn, dp), ctypes.byref(c), _ptr(head_cos, dp), _ptr(group_score, dp),
+        _ptr(tau, dp), _ptr(mask, ctypes.c_uint8))
+    if rc != 0:
+        raise RuntimeError("sr_oracle_route failed: %d" % rc)
+    return OracleResult(np.zeros((0,)), mask, head_cos, group_score, tau)
+
+
+def decode_splitk(q, k_cache, v_cache, seq_lens, bounds, *, tau_coef=(0.0, 0.0, 0.0, 0.55),
+                  len_norm: float = 0.0, sm_scale: float = 0.0, routing_enabled: bool = True,
+                  k0_norm=None, libpath: Optional[str] = None):
+    """Routed decode attention reached through Split-K partials and the log-sum-exp merge.
+
+    bounds: non-decreasing ints, bounds[0] == 0, bounds[-1] >= max(seq_lens).
+    Returns (out [B,Hq,D] fp64, mask, part_m [B,Hq,S], part_l [B,Hq,S]).
+    """
+    lib = _load(libpath)
+    q = np.ascontiguousarray(q)
+    B, Hq, D = q.shape
+    k_cache = np.ascontiguousarray(k_cache)
+    _, Hkv, Lmax, _ = k_cache.shape
+    q = _u16(q, (B, Hq, D))
+    k_cache = _u16(k_cache, (B, Hkv, Lmax, D))
+    v_cache = _u16(v_cache, (B, Hkv, Lmax, D))
+    sl = np.ascontiguousarray(np.asarray(seq_lens, dtype=np.int32))
+    bnd = np.ascontiguousarray(np.asarray(bounds, dtype=np.int32))
+    S = bnd.shape[0] - 1
+    c = _cfg(B, Hq, Hkv, D, Lmax, routing_enabled, False, sm_scale, tau_coef, len_norm)
+    out = np.empty((B, Hq, D), np.float64)
+    mask = np.empty((B, Hkv), np.uint8)
+    pm = np.empty((B, Hq, S), np.float64)
+    pl = np.empty((B, Hq, S), np.float64)
+    kn = None
+    if k0_norm is not None:
+        kn = np.ascontiguousarray(np.asarray(k0_norm, dtype=np.float64))
+    dp = ctypes.c_double
+    rc = lib.sr_oracle_decode_splitk(
+        _ptr(q, ctypes.c_uint16), _ptr(k_cache, ctypes.c_uint16), _ptr(v_cache, ctypes.c_uint16),
+        _ptr(sl, ctypes.c_int32), _ptr(kn, dp), ctypes.byref(c), _ptr(bnd, ctypes.c_int32),
+        ctypes.c_int32(S), _ptr(out, dp), _ptr(mask, ctypes.c_uint8), _ptr(pm, dp), _ptr(pl, dp))
+    if rc != 0:
+        raise RuntimeError("sr_oracle_decode_splitk failed: %d" % rc)
+    return out, mask, pm, pl
