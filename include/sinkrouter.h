@@ -1,0 +1,157 @@
+/*
+ * sinkrouter.h - C ABI of the MI355X (gfx950) SinkRouter decode-attention library.
+ *
+ * One decode step of one attention layer: a single query token per sequence attends
+ * over a long bf16 grouped-query KV cache.  Before any cache row beyond token 0 is
+ * read, each KV group is classified from the cosine between its query heads and the
+ * cached key of token 0; Sink Groups are written as zeros and their K/V are never
+ * loaded, Active Groups get exact softmax attention computed Split-K over the
+ * sequence and merged by log-sum-exp (paper Sections 4.2 and 4.3).
+ *
+ * Conventions for every entry point
+ *   - "device" pointers are HIP device memory on the current device, "host" pointers
+ *     are ordinary host memory.  The caller owns every buffer; the library allocates
+ *     no device memory and keeps no state between calls.
+ *   - bf16 tensors are raw 16-bit patterns, row-major, innermost dimension D, and must
+ *     be 16-byte aligned.
+ *   - Calls are asynchronous on params->stream and never synchronise (except the
+ *     *_profiled variant, which says so).  Buffers must stay alive until the stream
+ *     has passed the call.  Inputs are never written; outputs are fully overwritten.
+ *   - Every argument check runs on the host before the first HIP call, so error paths
+ *     need no GPU.  Return value: SR_OK (0) or a negative sr_status.
+ *   - No C++ exception crosses this boundary.  Concurrent calls are safe when they use
+ *     distinct workspaces and outputs.
+ */
+#ifndef SINKROUTER_H
+#define SINKROUTER_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum sr_status {
+  SR_OK = 0,
+  SR_ERR_NULL = -1,        /* a required pointer is NULL */
+  SR_ERR_SHAPE = -2,       /* sizes are non-positive, inconsistent or overflow */
+  SR_ERR_UNSUPPORTED = -3, /* head_dim != 128, group size > 16, kv_block != 64, bad struct_size */
+  SR_ERR_WORKSPACE = -4,   /* workspace missing, misaligned or smaller than required */
+  SR_ERR_ALIGN = -5,       /* a tensor pointer is not 16-byte aligned */
+  SR_ERR_HIP = -6          /* the HIP runtime reported an error (launch, event, ...) */
+} sr_status;
+
+/*
+ * Shape, routing rule and launch resources of one call.  Plain data, host memory.
+ *
+ * Routing rule (Section 4.2): for KV group g of sequence b with r = n_q_heads / n_kv_heads
+ * query heads, s_i = cos(q_{g,i}, K_0) (Eq. 8), S_g = mean_i s_i (Eq. 9), and the group is a
+ * Sink Group iff S_g > tau(L_b), strictly (Eq. 10), with the length-dependent threshold
+ * tau(x) = a x^3 + b x^2 + c x + d of Appendix A evaluated at x = seq_lens[b] / len_norm.
+ * The paper prints neither the coefficients nor the normalisation, so both are inputs; a
+ * fixed threshold t is {0,0,0,t} (the paper's operating point is 0.55).  K_0 is row 0 of the
+ * group's key cache.  A zero norm gives cosine 0; a NaN score leaves the group active.
+ */
+typedef struct sr_route_params {
+  uint32_t struct_size;     /* sizeof(sr_route_params); anything else -> SR_ERR_UNSUPPORTED */
+  int32_t batch;            /* B >= 1 */
+  int32_t n_q_heads;        /* H_q, a multiple of n_kv_heads; H_q / H_kv <= 16 */
+  int32_t n_kv_heads;       /* H_kv >= 1 */
+  int32_t head_dim;         /* D; only 128 is built */
+  int32_t max_seq_len;      /* L_max >= 1: token stride of both caches */
+  int32_t kv_block;         /* B_K, tokens per online-softmax block; only 64 is built */
+  int32_t num_splits;       /* Split-K chunks per sequence; 0 = choose automatically */
+  int32_t routing_enabled;  /* 0 = every group active (dense Split-K; the paper routes no
+                               group in its first two layers, Appendix B) */
+  float sm_scale;           /* softmax scale; 0 = 1/sqrt(D) */
+  float tau_coef[4];        /* a, b, c, d */
+  float len_norm;           /* x = seq_len / len_norm; <= 0 means x = 0 */
+  const float* k0_norm;     /* device, optional [B,H_kv]: ||K_0||_2 cached at prefill
+                               (Section 4.1); NULL = recompute from row 0 */
+  void* workspace;          /* device, 256-byte aligned, >= sinkrouter_workspace_bytes() */
+  size_t workspace_bytes;
+  void* stream;             /* hipStream_t; NULL = the default stream */
+} sr_route_params;
+
+/* The launch plan the library derives from the shape (host only, no GPU). */
+typedef struct sr_plan {
+  int32_t chunk_tokens;     /* tokens per Split-K chunk (multiple of 256) */
+  int32_t num_splits;       /* ceil(max_seq_len / chunk_tokens) */
+  int32_t group_size;       /* r = H_q / H_kv */
+  int32_t partial_grid;     /* workgroups of the Split-K partial kernel */
+  size_t workspace_bytes;
+} sr_plan;
+
+/*
+ * Fills *plan for params (workspace fields of params are ignored).  Split-K of
+ * Section 4.3: [0, L_max) is cut into num_splits chunks of chunk_tokens tokens; with
+ * params->num_splits == 0 the chunk is sized so the expected number of Active-Group
+ * chunks covers the chip several times.
+ */
+int sinkrouter_plan(const sr_route_params* params /*host*/, sr_plan* plan /*host*/);
+
+/* Bytes of device workspace sinkrouter_decode needs for params (0 if params are invalid). */
+size_t sinkrouter_workspace_bytes(const sr_route_params* params /*host*/);
+
+/*
+ * One routed decode step (Sections 4.2-4.3; Eq. 1 for Active Groups, Eq. 11 for Sink Groups).
+ *   q             device bf16 [B,H_q,D]; head h belongs to KV group h / r (the paper's
+ *                 [B,H_kv,G,D] layout, same memory)
+ *   k_cache       device bf16 [B,H_kv,L_max,D]
+ *   v_cache       device bf16 [B,H_kv,L_max,D]
+ *   seq_lens      device int32 [B]: valid rows per sequence, current token included;
+ *                 values outside [0,L_max] are clamped on the device.  Rows at or beyond
+ *                 seq_lens[b] are never read.
+ *   params        host
+ *   out           device bf16 [B,H_q,D]: softmax(scale q K^T) V for heads of Active Groups
+ *                 (fp32 accumulation, rounded to nearest even), exact zeros for heads of
+ *                 Sink Groups and for sequences of length 0
+ *   skip_mask_out device uint8 [B,H_kv]: 1 = Sink Group (skipped), 0 = Active Group
+ * Three kernels are enqueued on params->stream: routing probe, Split-K partial, merge.
+ */
+int sinkrouter_decode(const void* q, const void* k_cache, const void* v_cache,
+                      const int32_t* seq_lens, const sr_route_params* params,
+                      void* out, uint8_t* skip_mask_out);
+
+/*
+ * The routing decision alone (Section 4.2, Eq. 8-10): reads q and row 0 of k_cache only.
+ *   group_score_out device fp32 [B,H_kv], optional: S_g
+ *   skip_mask_out   device uint8 [B,H_kv]
+ * Needs no workspace.
+ */
+int sinkrouter_probe(const void* q, const void* k_cache, const int32_t* seq_lens,
+                     const sr_route_params* params, float* group_score_out,
+                     uint8_t* skip_mask_out);
+
+/*
+ * sinkrouter_decode with per-kernel timing, for benchmarks: HIP events are recorded on
+ * params->stream around each of the three kernels and the call SYNCHRONISES the stream
+ * before returning.  stage_us (host, 4 floats): probe, Split-K partial, merge, total, in
+ * microseconds.
+ */
+int sinkrouter_decode_profiled(const void* q, const void* k_cache, const void* v_cache,
+                               const int32_t* seq_lens, const sr_route_params* params,
+                               void* out, uint8_t* skip_mask_out, float* stage_us);
+
+/*
+ * Measurement helpers (no part of the method): a streaming read of `bytes` bytes of device
+ * memory (128-bit loads, every byte read once, one 4-byte result per workgroup written to
+ * sink, which must hold at least 4096 bytes), and a plain device-to-device copy kernel of
+ * known traffic used to calibrate hardware byte counters.  bytes must be a multiple of 16
+ * and the pointers 16-byte aligned.
+ */
+int sinkrouter_hbm_read_probe(const void* buf, size_t bytes, void* sink, void* stream);
+int sinkrouter_hbm_copy_probe(void* dst, const void* src, size_t bytes, void* stream);
+
+/* Static, human-readable text for a status code. */
+const char* sinkrouter_status_string(int status);
+
+/* ABI version of this header: bumped on any incompatible change. */
+int sinkrouter_abi_version(void);
+#define SINKROUTER_ABI_VERSION 1
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SINKROUTER_H */

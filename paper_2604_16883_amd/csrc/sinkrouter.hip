@@ -1,0 +1,615 @@
+// SinkRouter decode attention for MI355X (gfx950, CDNA4): kernels and the C ABI.
+//
+// Three kernels per decode step, all on the caller's stream:
+//   sr_probe_kernel    routing signal of Section 4.2 (Eq. 8-10): one wavefront per
+//                      (sequence, KV group) reads the group's query heads and row 0 of K.
+//   sr_partial_kernel  Split-K partial attention of Section 4.3 for Active Groups only.
+//                      Workgroup = (chunk, sequence, KV group); it leaves at once when the
+//                      group is a Sink Group.  Each of its 4 wavefronts streams 64-token
+//                      K/V blocks straight from HBM into registers with 128-bit loads and
+//                      feeds them to the matrix cores: all query heads of the group form
+//                      the N dimension of the MFMA tile, so one K/V fetch serves every
+//                      head of the group without expansion (the paper's group-centric
+//                      layout) and without an LDS round trip.  Online softmax per block.
+//                      The 4 wavefronts' results are merged through LDS into one partial
+//                      (m, l, o) per (head, chunk).
+//   sr_combine_kernel  log-sum-exp merge of the chunks, bf16 output; zeros for Sink Groups
+//                      (Eq. 11).
+//
+// Register layouts of the two MFMA shapes used (lane = 0..63, r16 = lane % 16, kg = lane / 16):
+//   v_mfma_f32_16x16x32_bf16  A: row r16, 8 consecutive k of k-group kg; B: column r16, same k;
+//                             D: column r16, rows 4*kg + {0,1,2,3} in the 4 result registers.
+//   v_mfma_f32_16x16x4_f32    A: row r16, k = kg; B: column r16, k = kg; D as above.
+// Only "A row = lane%16, B column = lane%16, both operands use the same k slot" is relied on,
+// so any consistent assignment of head-dimension elements to k slots gives the right dot product.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "sinkrouter.h"
+
+namespace {
+
+constexpr int kD = 128;          // head dimension
+constexpr int kBlock = 64;       // tokens per online-softmax block (B_K)
+constexpr int kWaves = 4;        // wavefronts per partial workgroup
+constexpr int kMaxGroup = 16;    // query heads per KV group that fit the MFMA tile
+constexpr int kChunkUnit = kBlock * kWaves;
+constexpr int kOStride = kD + 4; // LDS row stride (floats) of the per-wave output tile
+constexpr int kCombineThreads = 1024;
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0u;
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o, 64);
+  return x;
+}
+
+__device__ __forceinline__ int clamp_len(int L, int Lmax) { return L < 0 ? 0 : (L > Lmax ? Lmax : L); }
+
+// ------------------------------------------------------------------------------------------
+// Routing probe.  grid = B*H_kv, block = 64.  Lane l owns head-dimension elements 2l, 2l+1.
+// ------------------------------------------------------------------------------------------
+struct ProbeArgs {
+  const uint32_t* q;       // bf16 pairs
+  const uint32_t* k;
+  const int32_t* seq_lens;
+  const float* k0_norm;    // optional
+  float* group_score;      // optional
+  uint8_t* mask;
+  int Hq, Hkv, G, Lmax, routing;
+  float tau[4], len_norm;
+};
+
+__global__ __launch_bounds__(64) void sr_probe_kernel(ProbeArgs a) {
+  const int bg = blockIdx.x;
+  const int b = bg / a.Hkv, g = bg - b * a.Hkv;
+  const int lane = threadIdx.x;
+  const int L = clamp_len(a.seq_lens[b], a.Lmax);
+  const uint32_t kw = a.k[(size_t)bg * a.Lmax * (kD / 2) + lane];   // row 0 of the group's keys
+  const float k0 = bf16_lo(kw), k1 = bf16_hi(kw);
+  float kk = wave_sum(k0 * k0 + k1 * k1);
+  const float nk = a.k0_norm ? a.k0_norm[bg] : sqrtf(kk);
+  float S = 0.f;
+  for (int i = 0; i < a.G; ++i) {
+    const uint32_t qw = a.q[((size_t)b * a.Hq + (size_t)g * a.G + i) * (kD / 2) + lane];
+    const float q0 = bf16_lo(qw), q1 = bf16_hi(qw);
+    const float dot = wave_sum(q0 * k0 + q1 * k1);
+    const float qq = wave_sum(q0 * q0 + q1 * q1);
+    const float den = sqrtf(qq) * nk;
+    S += (den > 0.f) ? dot / den : 0.f;
+  }
+  S /= (float)a.G;
+  const float x = a.len_norm > 0.f ? (float)L / a.len_norm : 0.f;
+  const float tau = ((a.tau[0] * x + a.tau[1]) * x + a.tau[2]) * x + a.tau[3];
+  if (lane == 0) {
+    if (a.group_score) a.group_score[bg] = S;
+    a.mask[bg] = (a.routing && L > 0 && S > tau) ? 1 : 0;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Split-K partial.  grid = (num_splits, B*H_kv), block = 256 (4 wavefronts).
+// ------------------------------------------------------------------------------------------
+struct PartialArgs {
+  const uint16_t* q;
+  const uint16_t* k;
+  const uint16_t* v;
+  const int32_t* seq_lens;
+  const uint8_t* mask;
+  float* part_o;    // [B,Hq,S,D]  sum_t 2^(z_t - m) v_t
+  float* part_ml;   // [B,Hq,S,2]  m (log2 domain), l
+  int Hq, Hkv, G, Lmax, chunk, S;
+  float scale_log2;  // softmax scale * log2(e)
+};
+
+// K tile T, step j: lane (r16, kg) holds token tok0+16T+r16, elements (4j+kg)*8 .. +8.
+// Rows are clamped to the last valid one, so a ragged tail never reads beyond seq_len.
+__device__ __forceinline__ void load_k_block(uint4 (&kr)[4][4], const uint4* __restrict__ K4, int tok0,
+                                             int r16, int kg, int last) {
+#pragma unroll
+  for (int T = 0; T < 4; ++T) {
+    int row = tok0 + 16 * T + r16;
+    row = row < last ? row : last;
+    const uint4* p = K4 + (size_t)row * 16 + kg;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) kr[T][j] = p[4 * j];
+  }
+}
+
+// V tile T, row r: lane (r16, kg) holds token tok0+16T+4kg+r, elements 8*r16 .. +8.
+__device__ __forceinline__ void load_v_block(uint4 (&vr)[4][4], const uint4* __restrict__ V4, int tok0,
+                                             int r16, int kg, int last) {
+#pragma unroll
+  for (int T = 0; T < 4; ++T) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      int row = tok0 + 16 * T + 4 * kg + r;
+      row = row < last ? row : last;
+      vr[T][r] = V4[(size_t)row * 16 + r16];
+    }
+  }
+}
+
+struct WaveState {
+  float m_run;     // running max of head r16 (log2 domain), same in the 4 lane groups
+  float l_run;     // this lane's share of the running sum
+  f32x4 acc[8];    // acc[e][vv] = O[head r16][32*kg + 8*vv + e]
+};
+
+// One 64-token block: scores, online softmax, P.V.  With kPrefetch the loads of the block at
+// `next` are issued as soon as the registers they overwrite have been consumed, so the loop
+// body has no conditional loads and the wait counts the compiler inserts stay exact.
+template <bool kPrefetch>
+__device__ __forceinline__ void block_step(WaveState& w, uint4 (&kr)[4][4], uint4 (&vr)[4][4], const bf16x8 (&qb)[4],
+                                           const uint4* __restrict__ K4, const uint4* __restrict__ V4,
+                                           int tok0, int next, int t_end, int last, int r16, int kg,
+                                           float scale_log2) {
+  // ---- scores: sc[T][r] = q_{r16} . k_{tok0+16T+4kg+r}
+  f32x4 sc[4];
+#pragma unroll
+  for (int T = 0; T < 4; ++T) {
+    sc[T] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      sc[T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kr[T][j]), qb[j], sc[T], 0, 0, 0);
+  }
+  // The scheduler must not hoist the prefetch above the MFMAs that still read these registers
+  // (it would need a second register set) nor sink it below the softmax.
+  __builtin_amdgcn_sched_barrier(0);
+  if (kPrefetch) load_k_block(kr, K4, next, r16, kg, last);
+  __builtin_amdgcn_sched_barrier(0);
+  // ---- online softmax over the block
+  float bm = -INFINITY;
+#pragma unroll
+  for (int T = 0; T < 4; ++T)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int tok = tok0 + 16 * T + 4 * kg + r;
+      float z = sc[T][r] * scale_log2;
+      z = tok < t_end ? z : -INFINITY;
+      sc[T][r] = z;
+      bm = fmaxf(bm, z);
+    }
+  bm = fmaxf(bm, __shfl_xor(bm, 16, 64));
+  bm = fmaxf(bm, __shfl_xor(bm, 32, 64));
+  const float m_new = fmaxf(w.m_run, bm);
+  const float alpha = __builtin_amdgcn_exp2f(w.m_run - m_new);
+  float ps = 0.f;
+#pragma unroll
+  for (int T = 0; T < 4; ++T)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const float p = __builtin_amdgcn_exp2f(sc[T][r] - m_new);
+      sc[T][r] = p;
+      ps += p;
+    }
+  w.l_run = w.l_run * alpha + ps;
+  w.m_run = m_new;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) w.acc[e] *= alpha;
+  // ---- O^T += V^T P^T : A = V^T (row = dim column r16, k = lane group), B = P^T
+#pragma unroll
+  for (int T = 0; T < 4; ++T)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const uint4 x = vr[T][r];
+      const float p = sc[T][r];
+      w.acc[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(bf16_lo(x.x), p, w.acc[0], 0, 0, 0);
+      w.acc[1] = __builtin_amdgcn_mfma_f32_16x16x4f32(bf16_hi(x.x), p, w.acc[1], 0, 0, 0);
+      w.acc[2] = __builtin_amdgcn_mfma_f32_16x16x4f32(bf16_lo(x.y), p, w.acc[2], 0, 0, 0);
+      w.acc[3] = __builtin_amdgcn_mfma_f32_16x16x4f32(bf16_hi(x.y), p, w.acc[3], 0, 0, 0);
+      w.acc[4] = __builtin_amdgcn_mfma_f32_16x16x4f32(bf16_lo(x.z), p, w.acc[4], 0, 0, 0);
+      w.acc[5] = __builtin_amdgcn_mfma_f32_16x16x4f32(bf16_hi(x.z), p, w.acc[5], 0, 0, 0);
+      w.acc[6] = __builtin_amdgcn_mfma_f32_16x16x4f32(bf16_lo(x.w), p, w.acc[6], 0, 0, 0);
+      w.acc[7] = __builtin_amdgcn_mfma_f32_16x16x4f32(bf16_hi(x.w), p, w.acc[7], 0, 0, 0);
+    }
+  __builtin_amdgcn_sched_barrier(0);
+  if (kPrefetch) load_v_block(vr, V4, next, r16, kg, last);
+  __builtin_amdgcn_sched_barrier(0);
+}
+
+__global__ __launch_bounds__(256, 2) void sr_partial_kernel(PartialArgs a) {
+  const int s = blockIdx.x;
+  const int bg = blockIdx.y;
+  if (a.mask[bg]) return;                       // Sink Group: no K/V row is touched
+  const int b = bg / a.Hkv, g = bg - b * a.Hkv;
+  const int L = clamp_len(a.seq_lens[b], a.Lmax);
+  const int t_begin = s * a.chunk;
+  if (t_begin >= L) return;                     // chunk lies beyond this sequence
+  const int t_end = min(t_begin + a.chunk, L);
+  const int last = L - 1;
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r16 = lane & 15, kg = lane >> 4;
+  const int G = a.G;
+
+  // B operand of Q.K^T: column r16 = query head (zero beyond the group), same k slots as K.
+  bf16x8 qb[4];
+  {
+    const bool ok = r16 < G;
+    const uint4* qrow = reinterpret_cast<const uint4*>(a.q + ((size_t)b * a.Hq + (size_t)g * G + (ok ? r16 : 0)) * kD);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      uint4 x = qrow[4 * j + kg];
+      if (!ok) x = make_uint4(0, 0, 0, 0);
+      qb[j] = __builtin_bit_cast(bf16x8, x);
+    }
+  }
+  const uint4* K4 = reinterpret_cast<const uint4*>(a.k + (size_t)bg * a.Lmax * kD);
+  const uint4* V4 = reinterpret_cast<const uint4*>(a.v + (size_t)bg * a.Lmax * kD);
+
+  WaveState w;
+  w.m_run = -INFINITY;
+  w.l_run = 0.f;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) w.acc[e] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  int tok0 = t_begin + wave * kBlock;
+  if (tok0 < t_end) {
+    uint4 kr[4][4], vr[4][4];
+    load_k_block(kr, K4, tok0, r16, kg, last);
+    load_v_block(vr, V4, tok0, r16, kg, last);
+    int next = tok0 + kWaves * kBlock;
+    while (next < t_end) {
+      block_step<true>(w, kr, vr, qb, K4, V4, tok0, next, t_end, last, r16, kg, a.scale_log2);
+      tok0 = next;
+      next += kWaves * kBlock;
+    }
+    block_step<false>(w, kr, vr, qb, K4, V4, tok0, next, t_end, last, r16, kg, a.scale_log2);
+  }
+  float m_run = w.m_run, l_run = w.l_run;
+  f32x4 (&acc)[8] = w.acc;
+
+  // ---- merge the 4 wavefronts through LDS, write one partial per head
+  __shared__ float lds_o[kWaves][kMaxGroup][kOStride];
+  __shared__ float lds_m[kWaves][kMaxGroup];
+  __shared__ float lds_l[kWaves][kMaxGroup];
+  l_run += __shfl_xor(l_run, 16, 64);
+  l_run += __shfl_xor(l_run, 32, 64);
+  if (r16 < G) {
+    float* row = &lds_o[wave][r16][32 * kg];
+#pragma unroll
+    for (int vv = 0; vv < 4; ++vv) {
+      *reinterpret_cast<float4*>(row + 8 * vv) = make_float4(acc[0][vv], acc[1][vv], acc[2][vv], acc[3][vv]);
+      *reinterpret_cast<float4*>(row + 8 * vv + 4) = make_float4(acc[4][vv], acc[5][vv], acc[6][vv], acc[7][vv]);
+    }
+    if (kg == 0) { lds_m[wave][r16] = m_run; lds_l[wave][r16] = l_run; }
+  }
+  __syncthreads();
+  const int c4 = threadIdx.x & 31;            // float4 column
+  for (int h = threadIdx.x >> 5; h < G; h += 8) {
+    float M = lds_m[0][h];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) M = fmaxf(M, lds_m[w][h]);
+    float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+    float l = 0.f;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+      const float wt = __builtin_amdgcn_exp2f(lds_m[w][h] - M);   // wave 0 always holds a block, so M is finite
+      const float4 x = *reinterpret_cast<const float4*>(&lds_o[w][h][4 * c4]);
+      o.x += wt * x.x; o.y += wt * x.y; o.z += wt * x.z; o.w += wt * x.w;
+      l += wt * lds_l[w][h];
+    }
+    const size_t slot = ((size_t)b * a.Hq + (size_t)g * G + h) * a.S + s;
+    *reinterpret_cast<float4*>(a.part_o + slot * kD + 4 * c4) = o;
+    if (c4 == 0) *reinterpret_cast<float2*>(a.part_ml + slot * 2) = make_float2(M, l);
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Merge of the chunks.  grid = B*H_q, block = 1024 (16 wavefronts; lane owns 2 columns).
+// ------------------------------------------------------------------------------------------
+struct CombineArgs {
+  const float* part_o;
+  const float* part_ml;
+  const int32_t* seq_lens;
+  const uint8_t* mask;
+  uint32_t* out;    // bf16 pairs
+  int Hq, Hkv, G, Lmax, chunk, S;
+};
+
+__global__ __launch_bounds__(kCombineThreads) void sr_combine_kernel(CombineArgs a) {
+  constexpr int NW = kCombineThreads / 64;
+  const int bh = blockIdx.x;
+  const int b = bh / a.Hq, h = bh - b * a.Hq, g = h / a.G;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int L = clamp_len(a.seq_lens[b], a.Lmax);
+  uint32_t* orow = a.out + (size_t)bh * (kD / 2);
+  if (a.mask[b * a.Hkv + g] || L == 0) {        // zero surrogate (Eq. 11) / empty sequence
+    if (wave == 0) orow[lane] = 0u;
+    return;
+  }
+  const int nvalid = (L + a.chunk - 1) / a.chunk;
+  const float2* ml = reinterpret_cast<const float2*>(a.part_ml) + (size_t)bh * a.S;
+  const float2* po = reinterpret_cast<const float2*>(a.part_o) + (size_t)bh * a.S * (kD / 2);
+
+  __shared__ float red_m[NW];
+  __shared__ float red_l[NW];
+  __shared__ float2 red_o[NW][64];
+  float mx = -INFINITY;
+  for (int s = threadIdx.x; s < nvalid; s += kCombineThreads) mx = fmaxf(mx, ml[s].x);
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+  if (lane == 0) red_m[wave] = mx;
+  __syncthreads();
+  float M = red_m[0];
+#pragma unroll
+  for (int w = 1; w < NW; ++w) M = fmaxf(M, red_m[w]);
+
+  float2 acc = make_float2(0.f, 0.f);
+  float lsum = 0.f;
+#pragma unroll 4
+  for (int s = wave; s < nvalid; s += NW) {
+    const float2 st = ml[s];
+    const float wt = __builtin_amdgcn_exp2f(st.x - M);
+    const float2 o = po[(size_t)s * (kD / 2) + lane];
+    acc.x += wt * o.x;
+    acc.y += wt * o.y;
+    lsum += wt * st.y;
+  }
+  red_o[wave][lane] = acc;
+  if (lane == 0) red_l[wave] = lsum;
+  __syncthreads();
+  if (wave == 0) {
+    float2 t = red_o[0][lane];
+    float l = red_l[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) { t.x += red_o[w][lane].x; t.y += red_o[w][lane].y; l += red_l[w]; }
+    const float inv = 1.0f / l;
+    orow[lane] = f32_to_bf16_rne(t.x * inv) | (f32_to_bf16_rne(t.y * inv) << 16);
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Measurement helpers.
+// ------------------------------------------------------------------------------------------
+constexpr int kProbeGrid = 1024;
+
+__global__ __launch_bounds__(256) void sr_read_probe_kernel(const uint4* __restrict__ p, size_t n16, uint32_t* sink) {
+  uint32_t x = 0;
+  const size_t stride = (size_t)gridDim.x * 256;
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  for (; i + 3 * stride < n16; i += 4 * stride) {
+    const uint4 a = p[i], b = p[i + stride], c = p[i + 2 * stride], d = p[i + 3 * stride];
+    x ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+  }
+  for (; i < n16; i += stride) { const uint4 a = p[i]; x ^= a.x ^ a.y ^ a.z ^ a.w; }
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) x ^= __shfl_xor(x, o, 64);
+  __shared__ uint32_t red[4];
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = x;
+  __syncthreads();
+  if (threadIdx.x == 0) sink[blockIdx.x] = red[0] ^ red[1] ^ red[2] ^ red[3];
+}
+
+__global__ __launch_bounds__(256) void sr_copy_probe_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t n16) {
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+// ------------------------------------------------------------------------------------------
+// Host side.
+// ------------------------------------------------------------------------------------------
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+struct Layout {
+  sr_plan plan;
+  size_t off_o, off_ml, off_score;
+};
+
+int make_layout(const sr_route_params* p, Layout* lay) {
+  if (!p) return SR_ERR_NULL;
+  if (p->struct_size != sizeof(sr_route_params)) return SR_ERR_UNSUPPORTED;
+  if (p->batch < 1 || p->n_q_heads < 1 || p->n_kv_heads < 1 || p->max_seq_len < 1 || p->num_splits < 0)
+    return SR_ERR_SHAPE;
+  if (p->n_q_heads % p->n_kv_heads != 0) return SR_ERR_SHAPE;
+  if ((int64_t)p->batch * p->n_kv_heads > 65535) return SR_ERR_SHAPE;
+  if ((int64_t)p->batch * p->n_q_heads > (int64_t)1 << 24) return SR_ERR_SHAPE;
+  if (p->max_seq_len > (1 << 24)) return SR_ERR_SHAPE;          // 32-bit token arithmetic stays exact
+  if (p->head_dim != kD || p->kv_block != kBlock) return SR_ERR_UNSUPPORTED;
+  const int G = p->n_q_heads / p->n_kv_heads;
+  if (G > kMaxGroup) return SR_ERR_UNSUPPORTED;
+  if (!(p->sm_scale >= 0.f) || p->sm_scale > 1e30f) return SR_ERR_SHAPE;
+
+  int chunk;
+  if (p->num_splits > 0) {
+    const int per = (p->max_seq_len + p->num_splits - 1) / p->num_splits;
+    chunk = (int)align_up((size_t)per, kChunkUnit);
+  } else {
+    // Size chunks so that, with about 40% of the groups active (the paper's retained budget,
+    // Section 5.1), roughly 2048 workgroups have work: 8 per compute unit.
+    const double active_tokens = 0.4 * (double)p->batch * p->n_kv_heads * p->max_seq_len;
+    int units = (int)(active_tokens / (2048.0 * kChunkUnit));
+    units = units < 1 ? 1 : (units > 8 ? 8 : units);
+    chunk = units * kChunkUnit;
+  }
+  const int S = (p->max_seq_len + chunk - 1) / chunk;
+  lay->plan.chunk_tokens = chunk;
+  lay->plan.num_splits = S;
+  lay->plan.group_size = G;
+  lay->plan.partial_grid = S * p->batch * p->n_kv_heads;
+  const size_t heads = (size_t)p->batch * p->n_q_heads;
+  lay->off_o = 0;
+  lay->off_ml = align_up(heads * S * kD * sizeof(float), 256);
+  lay->off_score = lay->off_ml + align_up(heads * S * 2 * sizeof(float), 256);
+  lay->plan.workspace_bytes = lay->off_score + align_up((size_t)p->batch * p->n_kv_heads * sizeof(float), 256);
+  return SR_OK;
+}
+
+inline bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
+
+int launch_probe(const void* q, const void* k, const int32_t* seq_lens, const sr_route_params* p,
+                 const Layout& lay, float* score, uint8_t* mask, hipStream_t st) {
+  ProbeArgs a;
+  a.q = static_cast<const uint32_t*>(q);
+  a.k = static_cast<const uint32_t*>(k);
+  a.seq_lens = seq_lens;
+  a.k0_norm = p->k0_norm;
+  a.group_score = score;
+  a.mask = mask;
+  a.Hq = p->n_q_heads; a.Hkv = p->n_kv_heads; a.G = lay.plan.group_size; a.Lmax = p->max_seq_len;
+  a.routing = p->routing_enabled != 0;
+  for (int i = 0; i < 4; ++i) a.tau[i] = p->tau_coef[i];
+  a.len_norm = p->len_norm;
+  hipLaunchKernelGGL(sr_probe_kernel, dim3(p->batch * p->n_kv_heads), dim3(64), 0, st, a);
+  return hipGetLastError() == hipSuccess ? SR_OK : SR_ERR_HIP;
+}
+
+int decode_impl(const void* q, const void* k, const void* v, const int32_t* seq_lens,
+                const sr_route_params* p, void* out, uint8_t* mask, float* stage_us) {
+  if (!q || !k || !v || !seq_lens || !p || !out || !mask) return SR_ERR_NULL;
+  Layout lay;
+  int rc = make_layout(p, &lay);
+  if (rc != SR_OK) return rc;
+  if (misaligned(q, 16) || misaligned(k, 16) || misaligned(v, 16) || misaligned(out, 16) || misaligned(seq_lens, 4))
+    return SR_ERR_ALIGN;
+  if (!p->workspace || misaligned(p->workspace, 256) || p->workspace_bytes < lay.plan.workspace_bytes)
+    return SR_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(p->stream);
+  char* ws = static_cast<char*>(p->workspace);
+  float* part_o = reinterpret_cast<float*>(ws + lay.off_o);
+  float* part_ml = reinterpret_cast<float*>(ws + lay.off_ml);
+  float* score = reinterpret_cast<float*>(ws + lay.off_score);
+
+  hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
+  if (stage_us) {
+    for (int i = 0; i < 4; ++i)
+      if (hipEventCreate(&ev[i]) != hipSuccess) {
+        for (int j = 0; j < i; ++j) (void)hipEventDestroy(ev[j]);
+        return SR_ERR_HIP;
+      }
+  }
+  auto mark = [&](int i) { return !stage_us || hipEventRecord(ev[i], st) == hipSuccess; };
+  bool ok = mark(0);
+  if (ok) ok = launch_probe(q, k, seq_lens, p, lay, score, mask, st) == SR_OK;
+  if (ok) ok = mark(1);
+  if (ok) {
+    PartialArgs a;
+    a.q = static_cast<const uint16_t*>(q);
+    a.k = static_cast<const uint16_t*>(k);
+    a.v = static_cast<const uint16_t*>(v);
+    a.seq_lens = seq_lens; a.mask = mask; a.part_o = part_o; a.part_ml = part_ml;
+    a.Hq = p->n_q_heads; a.Hkv = p->n_kv_heads; a.G = lay.plan.group_size; a.Lmax = p->max_seq_len;
+    a.chunk = lay.plan.chunk_tokens; a.S = lay.plan.num_splits;
+    const float scale = p->sm_scale > 0.f ? p->sm_scale : 0.08838834764831845f;   // 1/sqrt(128)
+    a.scale_log2 = scale * 1.4426950408889634f;
+    hipLaunchKernelGGL(sr_partial_kernel, dim3(lay.plan.num_splits, p->batch * p->n_kv_heads), dim3(64 * kWaves), 0, st, a);
+    ok = hipGetLastError() == hipSuccess;
+  }
+  if (ok) ok = mark(2);
+  if (ok) {
+    CombineArgs c;
+    c.part_o = part_o; c.part_ml = part_ml; c.seq_lens = seq_lens; c.mask = mask;
+    c.out = static_cast<uint32_t*>(out);
+    c.Hq = p->n_q_heads; c.Hkv = p->n_kv_heads; c.G = lay.plan.group_size; c.Lmax = p->max_seq_len;
+    c.chunk = lay.plan.chunk_tokens; c.S = lay.plan.num_splits;
+    hipLaunchKernelGGL(sr_combine_kernel, dim3(p->batch * p->n_q_heads), dim3(kCombineThreads), 0, st, c);
+    ok = hipGetLastError() == hipSuccess;
+  }
+  if (ok) ok = mark(3);
+  if (stage_us) {
+    if (ok) ok = hipEventSynchronize(ev[3]) == hipSuccess;
+    if (ok) {
+      for (int i = 0; i < 3 && ok; ++i) {
+        float ms = 0.f;
+        ok = hipEventElapsedTime(&ms, ev[i], ev[i + 1]) == hipSuccess;
+        stage_us[i] = ms * 1000.f;
+      }
+      float ms = 0.f;
+      if (ok) ok = hipEventElapsedTime(&ms, ev[0], ev[3]) == hipSuccess;
+      stage_us[3] = ms * 1000.f;
+    }
+    for (int i = 0; i < 4; ++i) (void)hipEventDestroy(ev[i]);
+  }
+  return ok ? SR_OK : SR_ERR_HIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+int sinkrouter_plan(const sr_route_params* params, sr_plan* plan) {
+  if (!params || !plan) return SR_ERR_NULL;
+  Layout lay;
+  const int rc = make_layout(params, &lay);
+  if (rc != SR_OK) return rc;
+  *plan = lay.plan;
+  return SR_OK;
+}
+
+size_t sinkrouter_workspace_bytes(const sr_route_params* params) {
+  Layout lay;
+  if (make_layout(params, &lay) != SR_OK) return 0;
+  return lay.plan.workspace_bytes;
+}
+
+int sinkrouter_decode(const void* q, const void* k_cache, const void* v_cache, const int32_t* seq_lens,
+                      const sr_route_params* params, void* out, uint8_t* skip_mask_out) {
+  return decode_impl(q, k_cache, v_cache, seq_lens, params, out, skip_mask_out, nullptr);
+}
+
+int sinkrouter_decode_profiled(const void* q, const void* k_cache, const void* v_cache, const int32_t* seq_lens,
+                               const sr_route_params* params, void* out, uint8_t* skip_mask_out,
+                               float* stage_us) {
+  if (!stage_us) return SR_ERR_NULL;
+  return decode_impl(q, k_cache, v_cache, seq_lens, params, out, skip_mask_out, stage_us);
+}
+
+int sinkrouter_probe(const void* q, const void* k_cache, const int32_t* seq_lens,
+                     const sr_route_params* params, float* group_score_out, uint8_t* skip_mask_out) {
+  if (!q || !k_cache || !seq_lens || !params || !skip_mask_out) return SR_ERR_NULL;
+  Layout lay;
+  const int rc = make_layout(params, &lay);
+  if (rc != SR_OK) return rc;
+  if (misaligned(q, 16) || misaligned(k_cache, 16) || misaligned(seq_lens, 4) || misaligned(group_score_out, 4))
+    return SR_ERR_ALIGN;
+  return launch_probe(q, k_cache, seq_lens, params, lay, group_score_out, skip_mask_out,
+                      static_cast<hipStream_t>(params->stream));
+}
+
+int sinkrouter_hbm_read_probe(const void* buf, size_t bytes, void* sink, void* stream) {
+  if (!buf || !sink) return SR_ERR_NULL;
+  if (bytes == 0 || bytes % 16 != 0) return SR_ERR_SHAPE;
+  if (misaligned(buf, 16) || misaligned(sink, 4)) return SR_ERR_ALIGN;
+  hipLaunchKernelGGL(sr_read_probe_kernel, dim3(kProbeGrid), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     static_cast<const uint4*>(buf), bytes / 16, static_cast<uint32_t*>(sink));
+  return hipGetLastError() == hipSuccess ? SR_OK : SR_ERR_HIP;
+}
+
+int sinkrouter_hbm_copy_probe(void* dst, const void* src, size_t bytes, void* stream) {
+  if (!dst || !src) return SR_ERR_NULL;
+  if (bytes == 0 || bytes % 16 != 0) return SR_ERR_SHAPE;
+  if (misaligned(dst, 16) || misaligned(src, 16)) return SR_ERR_ALIGN;
+  hipLaunchKernelGGL(sr_copy_probe_kernel, dim3(kProbeGrid * 2), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     static_cast<uint4*>(dst), static_cast<const uint4*>(src), bytes / 16);
+  return hipGetLastError() == hipSuccess ? SR_OK : SR_ERR_HIP;
+}
+
+const char* sinkrouter_status_string(int status) {
+  switch (status) {
+    case SR_OK: return "ok";
+    case SR_ERR_NULL: return "a required pointer is NULL";
+    case SR_ERR_SHAPE: return "invalid or inconsistent sizes";
+    case SR_ERR_UNSUPPORTED: return "unsupported configuration (head_dim must be 128, kv_block 64, group size <= 16, struct_size must match)";
+    case SR_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case SR_ERR_ALIGN: return "tensor pointer not 16-byte aligned";
+    case SR_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+int sinkrouter_abi_version(void) { return SINKROUTER_ABI_VERSION; }
+
+}  // extern "C"

@@ -1,0 +1,127 @@
+"""HIP path vs CPU oracle, element by element, through the C ABI (needs an MI355X)."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+import oracle
+from paper_2604_16883_amd import synth
+
+import gpu_util as gu
+
+
+def _check(sb, taus=None, label="", **kw):
+    G = sb.workload.group_size
+    dev = None
+    reports = []
+    for tau in (taus or sb.taus):
+        tc = (0, 0, 0, tau)
+        res = gu.run_hip(sb.q, sb.k, sb.v, sb.seq_lens, tau_coef=tc, dev=dev, **kw)
+        dev = res["dev"]
+        ref = oracle.decode(sb.q, sb.k, sb.v, sb.seq_lens, tau_coef=tc, want_dense=True,
+                            sm_scale=kw.get("sm_scale", 0.0), len_norm=kw.get("len_norm", 0.0),
+                            routing_enabled=kw.get("routing_enabled", True))
+        rep = gu.compare(res, ref, G, "%s tau=%.4f" % (label, tau))
+        reports.append(rep)
+        print(label, "tau=%.4f" % tau, rep, "splits", res["plan"].num_splits, "chunk", res["plan"].chunk_tokens, flush=True)
+    return reports
+
+
+# ---- reduced sizes: several tiles, ragged tails --------------------------------------------------
+REDUCED = [
+    ("c0", 4096, None),                       # the small config at its real size
+    ("c1", 1000, [1000, 937, 64, 1]),         # ragged batch, tails inside a tile and a block
+    ("c2", 3125, None),                       # G = 8, not a multiple of 64, secondary sinks
+    ("c3", 2049, None),                       # G = 8, 64 query heads, one token past a block
+    ("c4", 1500, [1500, 1217]),               # MHA (G = 1), image segments
+]
+
+
+@pytest.mark.parametrize("name,L,sl", REDUCED, ids=[r[0] for r in REDUCED])
+def test_reduced_routed_and_dense(name, L, sl):
+    w = synth.WORKLOADS[name].scaled(L)
+    sb = synth.generate(w, seq_lens=sl, max_seq_len=L + (37 if sl else 0))
+    reps = _check(sb, label=name + "-reduced")
+    assert any(0 < r["skip_ratio"] < 1 for r in reps)
+    _check(sb, taus=[0.55], label=name + "-reduced-dense", routing_enabled=False)
+
+
+@pytest.mark.parametrize("num_splits", [1, 2, 3, 7, 64])
+def test_output_independent_of_split_count(num_splits):
+    w = synth.WORKLOADS["c0"].scaled(1733)
+    sb = synth.generate(w, seed=11)
+    _check(sb, label="splits=%d" % num_splits, num_splits=num_splits)
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(16, 1), (8, 4), (6, 2), (3, 3), (12, 1)])
+def test_group_sizes(Hq, Hkv):
+    w = synth.Workload("g", 2, Hq, Hkv, 777, 0.6, base_seed=50 + Hq)
+    sb = synth.generate(w, seq_lens=[777, 300])
+    _check(sb, label="Hq%d/Hkv%d" % (Hq, Hkv))
+
+
+def test_edge_lengths():
+    # lengths 0 and 1, exactly one block, one block + 1, all with a poisoned tail beyond seq_len
+    w = synth.Workload("edge", 6, 8, 2, 300, 0.5, base_seed=77)
+    sl = [0, 1, 64, 65, 256, 257]
+    sb = synth.generate(w, seq_lens=sl, max_seq_len=300)
+    for tau in (0.55, -2.0, 2.0):
+        res = gu.run_hip(sb.q, sb.k, sb.v, sb.seq_lens, tau_coef=(0, 0, 0, tau))
+        ref = oracle.decode(sb.q, sb.k, sb.v, sb.seq_lens, tau_coef=(0, 0, 0, tau), want_dense=True)
+        rep = gu.compare(res, ref, 4, "edge tau=%g" % tau)
+        print("edge", tau, rep, flush=True)
+        assert res["mask"][0].tolist() == [0, 0]             # empty sequence: never a Sink Group
+        assert np.all(res["out_bits"][0] == 0)
+    # L = 1 and active: out = V_0 exactly (already bf16)
+    res = gu.run_hip(sb.q, sb.k, sb.v, sb.seq_lens, routing_enabled=False)
+    for h in range(8):
+        assert np.array_equal(res["out_bits"][1, h], sb.v[1, h // 4, 0])
+
+
+def test_threshold_cubic_scale_and_cached_norm():
+    w = synth.WORKLOADS["c1"].scaled(900, batch=3)
+    sb = synth.generate(w, seed=5, seq_lens=[900, 450, 200])
+    coef = (0.4, -0.9, 0.5, 0.45)
+    kw = dict(tau_coef=coef, len_norm=900.0, sm_scale=0.11)
+    res = gu.run_hip(sb.q, sb.k, sb.v, sb.seq_lens, **kw)
+    ref = oracle.decode(sb.q, sb.k, sb.v, sb.seq_lens, want_dense=True, **kw)
+    print("cubic", gu.compare(res, ref, 4, "cubic"), ref.tau, flush=True)
+    assert len(set(np.round(ref.tau, 6))) == 3
+    # cached anchor norm (Section 4.1): passing the true norm changes nothing; a doubled norm halves S
+    kn = np.linalg.norm(synth.bf16_bits_to_f32(sb.k[:, :, 0]).astype(np.float64), axis=-1)
+    res1 = gu.run_hip(sb.q, sb.k, sb.v, sb.seq_lens, k0_norm=kn, **kw)
+    np.testing.assert_allclose(res1["score"], res["score"], rtol=0, atol=1e-6)
+    res2 = gu.run_hip(sb.q, sb.k, sb.v, sb.seq_lens, k0_norm=2 * kn, **kw)
+    ref2 = oracle.decode(sb.q, sb.k, sb.v, sb.seq_lens, want_dense=True, k0_norm=2 * kn, **kw)
+    gu.compare(res2, ref2, 4, "doubled-norm")
+
+
+def test_mask_reads_token0_only_and_skip_bound():
+    w = synth.WORKLOADS["c0"].scaled(1024)
+    sb = synth.generate(w, seed=3)
+    base = gu.run_hip(sb.q, sb.k, sb.v, sb.seq_lens)
+    k2, v2 = sb.k.copy(), sb.v.copy()
+    rng = np.random.default_rng(1)
+    k2[:, :, 1:] = rng.integers(0, 0x4000, size=k2[:, :, 1:].shape, dtype=np.uint16)
+    v2[:] = rng.integers(0, 0x4000, size=v2.shape, dtype=np.uint16)
+    alt = gu.run_hip(sb.q, k2, v2, sb.seq_lens)
+    assert np.array_equal(alt["mask"], base["mask"])
+    assert np.array_equal(alt["score"], base["score"])
+    # Eq. 4 on the GPU's dense output: ||u|| <= alpha_0 ||v_0|| + (1 - alpha_0) max ||v_t||
+    dense = gu.run_hip(sb.q, sb.k, sb.v, sb.seq_lens, routing_enabled=False)
+    ref = oracle.decode(sb.q, sb.k, sb.v, sb.seq_lens, want_dense=True)
+    vf = synth.bf16_bits_to_f32(sb.v).astype(np.float64)
+    for h in range(w.n_q_heads):
+        g = h // w.group_size
+        bound = ref.alpha0[0, h] * np.linalg.norm(vf[0, g, 0]) + (1 - ref.alpha0[0, h]) * np.linalg.norm(vf[0, g, 1:], axis=-1).max()
+        assert np.linalg.norm(dense["out"][0, h]) <= bound + 1e-2
+
+
+# ---- full sizes, in the launch configuration the benchmark times -----------------------------------
+@pytest.mark.parametrize("name", ["c1", "c2", "c3", "c4"])
+def test_full_size(name):
+    w = synth.WORKLOADS[name]
+    sb = synth.generate(w)
+    print(name, "generated", sb.k.nbytes * 2 / 1e6, "MB", flush=True)
+    _check(sb, label=name + "-full")
+    _check(sb, taus=[0.55], label=name + "-full-dense", routing_enabled=False)
