@@ -136,7 +136,12 @@ def hbm_calibration(nbytes=2 << 30, reps=10):
         binding.sinkrouter_hbm_read_probe(buf, nbytes, sink)
     e1.record()
     torch.cuda.synchronize()
-    return nbytes * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    read_gbs = nbytes * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    # one plain copy of known size: the reference dispatch for scaling hardware byte counters
+    dst = torch.empty((nbytes // 2,), dtype=torch.uint8, device="cuda")
+    binding.sinkrouter_hbm_copy_probe(dst, buf, nbytes // 2)
+    torch.cuda.synchronize()
+    return read_gbs
 
 
 def cpu_baseline(sb, budget_s=20.0):
