@@ -28,23 +28,40 @@ HBM_PEAK_GBS = 8000.0     # MI355X published HBM3E bandwidth
 D = 128
 
 
+def partial_records(w, seq_lens, mask, plan):
+    """Number of (head, workgroup) partial records the Split-K kernel writes for this mask."""
+    B, Hq, Hkv = w.batch, w.n_q_heads, w.n_kv_heads
+    G = Hq // Hkv
+    if plan.schedule == 0:
+        return sum(G * ((int(seq_lens[b]) + plan.chunk_tokens - 1) // plan.chunk_tokens)
+                   for b in range(B) for g in range(Hkv) if not mask[b, g])
+    units = [0 if mask[b, g] else (int(seq_lens[b]) + 63) // 64 for b in range(B) for g in range(Hkv)]
+    U = sum(units)
+    if U == 0:
+        return 0
+    c = (U + plan.partial_grid - 1) // plan.partial_grid
+    n, s0 = 0, 0
+    for u in units:
+        if u:
+            n += G * ((s0 + u - 1) // c - s0 // c + 1)
+        s0 += u
+    return n
+
+
 def algorithmic_bytes(w, seq_lens, mask, plan):
     """Bytes the method itself must move in the Split-K partial kernel for this mask:
     K and V rows of every Active Group once (shared by the group's heads), the group's
-    queries, the routing byte, and the partial (m, l, o) records it writes."""
+    queries, the routing bytes, and the partial (m, l, o) records it writes."""
     B, Hq, Hkv = w.batch, w.n_q_heads, w.n_kv_heads
     G = Hq // Hkv
     total = 0
     for b in range(B):
-        L = int(seq_lens[b])
-        nsplit = (L + plan.chunk_tokens - 1) // plan.chunk_tokens
         for g in range(Hkv):
-            if mask[b, g]:
-                continue
-            total += L * D * 2 * 2                      # K + V rows
-            total += nsplit * G * (D + 2) * 4           # partial records written
-            total += G * D * 2                          # the group's queries (once)
-    total += B * Hkv                                     # skip bytes
+            if not mask[b, g]:
+                total += int(seq_lens[b]) * D * 2 * 2       # K + V rows
+                total += G * D * 2                          # the group's queries (once)
+    total += partial_records(w, seq_lens, mask, plan) * (D + 2) * 4
+    total += B * Hkv                                         # skip bytes
     return total
 
 
@@ -60,7 +77,7 @@ def time_steps(fn, steps, warmup):
     return (time.perf_counter() - t0) / steps * 1e6
 
 
-def run_workload(name, steps, warmup, copies, verbose):
+def run_workload(name, steps, warmup, copies, verbose, num_splits=0):
     import torch
     from paper_2604_16883_amd import binding, synth
     w = synth.WORKLOADS[name]
@@ -80,7 +97,8 @@ def run_workload(name, steps, warmup, copies, verbose):
     res = {"workload": name, "description": w.description, "gen_s": round(gen_s, 2), "copies": copies}
     modes = [("routed_tau0.55", True, 0.55)] + [("routed_tau%.3f" % t, True, t) for t in sb.taus[1:]] + [("dense", False, 0.55)]
     for label, routing, tau in modes:
-        p = binding.make_route_params(B, Hq, Hkv, Lmax, routing_enabled=routing, tau_coef=(0, 0, 0, tau))
+        p = binding.make_route_params(B, Hq, Hkv, Lmax, routing_enabled=routing, tau_coef=(0, 0, 0, tau),
+                                      num_splits=num_splits)
         plan = binding.sinkrouter_plan(p)
         ws = torch.empty((plan.workspace_bytes,), dtype=torch.uint8, device="cuda")
         p.workspace, p.workspace_bytes = ws.data_ptr(), plan.workspace_bytes
@@ -112,7 +130,8 @@ def run_workload(name, steps, warmup, copies, verbose):
             "algorithmic_bytes": int(ab),
             "partial_GBps": round(ab / partial_us / 1e3, 1),
             "step_GBps": round(ab / us / 1e3, 1),
-            "chunk_tokens": int(plan.chunk_tokens), "num_splits": int(plan.num_splits),
+            "schedule": "balanced" if plan.schedule else "fixed",
+            "partial_grid": int(plan.partial_grid), "partial_records": partial_records(w, sb.seq_lens, m, plan),
         }
         res[label] = r
         if verbose:
@@ -177,6 +196,7 @@ def main():
     ap.add_argument("--also", default="c1", help="comma list of further workloads to report ('' for none)")
     ap.add_argument("--copies", type=int, default=3, help="distinct K/V copies rotated through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--num-splits", type=int, default=0, help="0 = balanced schedule, >0 = fixed Split-K chunks")
     ap.add_argument("-v", "--verbose", action="store_true")
     a = ap.parse_args()
     if a.gpus != 1:
@@ -191,13 +211,13 @@ def main():
     binding.load()
 
     calib = hbm_calibration()
-    main_res, sb, _dev = run_workload(a.workload, a.steps, a.warmup, a.copies, a.verbose)
+    main_res, sb, _dev = run_workload(a.workload, a.steps, a.warmup, a.copies, a.verbose, a.num_splits)
     cpu = None if a.no_cpu_baseline else cpu_baseline(sb)
     del _dev
     torch.cuda.empty_cache()
     others = {}
     for name in [x for x in a.also.split(",") if x and x != a.workload]:
-        r, sb2, dev2 = run_workload(name, a.steps, a.warmup, max(a.copies, 4), a.verbose)
+        r, sb2, dev2 = run_workload(name, a.steps, a.warmup, max(a.copies, 4), a.verbose, a.num_splits)
         others[name] = r
         del sb2, dev2
         torch.cuda.empty_cache()
@@ -214,7 +234,7 @@ def main():
         "dtype": "bf16 in, fp32 accumulate", "data": "synthetic (seeded, sink-planted KV cache resident in HBM)",
         "config": {"workload": "%s: %s" % (a.workload, main_res["description"]), "kv_block": 64,
                    "threshold": 0.55, "skip_ratio": routed["skip_ratio"],
-                   "chunk_tokens": routed["chunk_tokens"], "num_splits": routed["num_splits"]},
+                   "schedule": routed["schedule"], "partial_grid": routed["partial_grid"]},
         "roofline": {"bound": "hbm", "kernel": "sr_partial_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
                      "algorithmic_bytes_per_launch": routed["algorithmic_bytes"],

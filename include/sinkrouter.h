@@ -61,7 +61,7 @@ typedef struct sr_route_params {
   int32_t head_dim;         /* D; only 128 is built */
   int32_t max_seq_len;      /* L_max >= 1: token stride of both caches */
   int32_t kv_block;         /* B_K, tokens per online-softmax block; only 64 is built */
-  int32_t num_splits;       /* Split-K chunks per sequence; 0 = choose automatically */
+  int32_t num_splits;       /* Split-K chunks per sequence; 0 = balanced schedule (sinkrouter_plan) */
   int32_t routing_enabled;  /* 0 = every group active (dense Split-K; the paper routes no
                                group in its first two layers, Appendix B) */
   float sm_scale;           /* softmax scale; 0 = 1/sqrt(D) */
@@ -76,18 +76,27 @@ typedef struct sr_route_params {
 
 /* The launch plan the library derives from the shape (host only, no GPU). */
 typedef struct sr_plan {
-  int32_t chunk_tokens;     /* tokens per Split-K chunk (multiple of 256) */
-  int32_t num_splits;       /* ceil(max_seq_len / chunk_tokens) */
+  int32_t schedule;         /* 1 = balanced, 0 = fixed chunks (see sinkrouter_plan) */
+  int32_t chunk_tokens;     /* fixed: tokens per Split-K chunk (multiple of 256); balanced: 0 */
+  int32_t num_splits;       /* fixed: ceil(max_seq_len / chunk_tokens); balanced: 0 */
   int32_t group_size;       /* r = H_q / H_kv */
   int32_t partial_grid;     /* workgroups of the Split-K partial kernel */
+  int32_t slots_per_head;   /* partial (m, l, o) records reserved per query head */
   size_t workspace_bytes;
 } sr_plan;
 
 /*
- * Fills *plan for params (workspace fields of params are ignored).  Split-K of
- * Section 4.3: [0, L_max) is cut into num_splits chunks of chunk_tokens tokens; with
- * params->num_splits == 0 the chunk is sized so the expected number of Active-Group
- * chunks covers the chip several times.
+ * Fills *plan for params (workspace fields of params are ignored).  Split-K of Section 4.3:
+ * the tokens of a sequence are cut into chunks, each chunk yields a partial result per head,
+ * and the partials are merged.  Two schedules:
+ *   params->num_splits > 0  "fixed": [0, L_max) is cut into num_splits equal chunks (rounded up
+ *                           to 256 tokens), one workgroup per (chunk, sequence, KV group), as
+ *                           the paper states it; workgroups of Sink Groups exit immediately.
+ *   params->num_splits == 0 "balanced": the 64-token blocks of the Active Groups only are dealt
+ *                           out in equal contiguous shares to a grid that just fills the chip
+ *                           (512 workgroups), so the chunk length adapts to the skip pattern.
+ *                           Needs B*H_kv <= 2048; larger batches fall back to fixed chunks.
+ * The result does not depend on the schedule beyond fp32 rounding.
  */
 int sinkrouter_plan(const sr_route_params* params /*host*/, sr_plan* plan /*host*/);
 

@@ -49,10 +49,12 @@ class RouteParams(ctypes.Structure):
 class Plan(ctypes.Structure):
     """Mirror of ``sr_plan``."""
     _fields_ = [
+        ("schedule", ctypes.c_int32),
         ("chunk_tokens", ctypes.c_int32),
         ("num_splits", ctypes.c_int32),
         ("group_size", ctypes.c_int32),
         ("partial_grid", ctypes.c_int32),
+        ("slots_per_head", ctypes.c_int32),
         ("workspace_bytes", ctypes.c_size_t),
     ]
 

@@ -1,19 +1,26 @@
 // SinkRouter decode attention for MI355X (gfx950, CDNA4): kernels and the C ABI.
 //
 // Three kernels per decode step, all on the caller's stream:
-//   sr_probe_kernel    routing signal of Section 4.2 (Eq. 8-10): one wavefront per
-//                      (sequence, KV group) reads the group's query heads and row 0 of K.
-//   sr_partial_kernel  Split-K partial attention of Section 4.3 for Active Groups only.
-//                      Workgroup = (chunk, sequence, KV group); it leaves at once when the
-//                      group is a Sink Group.  Each of its 4 wavefronts streams 64-token
-//                      K/V blocks straight from HBM into registers with 128-bit loads and
-//                      feeds them to the matrix cores: all query heads of the group form
-//                      the N dimension of the MFMA tile, so one K/V fetch serves every
-//                      head of the group without expansion (the paper's group-centric
-//                      layout) and without an LDS round trip.  Online softmax per block.
-//                      The 4 wavefronts' results are merged through LDS into one partial
-//                      (m, l, o) per (head, chunk).
-//   sr_combine_kernel  log-sum-exp merge of the chunks, bf16 output; zeros for Sink Groups
+//   sr_probe_kernel    routing signal of Section 4.2 (Eq. 8-10): one workgroup per
+//                      (sequence, KV group), one wavefront per query head; reads the
+//                      group's query heads and row 0 of K only.
+//   sr_partial_*       Split-K partial attention of Section 4.3 for Active Groups only.
+//                      Each wavefront streams 64-token K/V blocks straight from HBM into
+//                      registers with 128-bit loads and feeds them to the matrix cores: all
+//                      query heads of the group form the N dimension of the MFMA tile, so one
+//                      K/V fetch serves every head of the group without expansion (the
+//                      paper's group-centric layout) and without an LDS round trip.  Online
+//                      softmax per block.  The 4 wavefronts of a workgroup interleave blocks
+//                      and merge their results through LDS into one partial (m, l, o) per
+//                      (head, workgroup).  Two schedules:
+//        balanced  (default) a grid that just fills the chip; every workgroup first scans the
+//                  skip mask, so the 64-token blocks of the Active Groups only are dealt out
+//                  in equal contiguous shares.  Sink Groups cost nothing and the chip stays
+//                  full whatever the skip pattern is.
+//        fixed     the paper's literal Split-K: [0, L) cut into num_splits chunks, one
+//                  workgroup per (chunk, sequence, KV group); workgroups of Sink Groups
+//                  leave at once.
+//   sr_combine_kernel  log-sum-exp merge of the partials, bf16 output; zeros for Sink Groups
 //                      (Eq. 11).
 //
 // Register layouts of the two MFMA shapes used (lane = 0..63, r16 = lane % 16, kg = lane / 16):
@@ -27,18 +34,32 @@
 
 #include "sinkrouter.h"
 
+#ifndef SR_FINE_PREFETCH
+#define SR_FINE_PREFETCH 1
+#endif
+
 namespace {
 
-constexpr int kD = 128;          // head dimension
-constexpr int kBlock = 64;       // tokens per online-softmax block (B_K)
-constexpr int kWaves = 4;        // wavefronts per partial workgroup
-constexpr int kMaxGroup = 16;    // query heads per KV group that fit the MFMA tile
+constexpr int kD = 128;              // head dimension
+constexpr int kBlock = 64;           // tokens per online-softmax block (B_K)
+constexpr int kWaves = 4;            // wavefronts per partial workgroup
+constexpr int kMaxGroup = 16;        // query heads per KV group that fit the MFMA tile
 constexpr int kChunkUnit = kBlock * kWaves;
-constexpr int kOStride = kD + 4; // LDS row stride (floats) of the per-wave output tile
+constexpr int kOStride = kD + 4;     // LDS row stride (floats) of the per-wave output tile
 constexpr int kCombineThreads = 1024;
+constexpr int kBalancedGrid = 512;   // 256 compute units x 2 resident workgroups (228 VGPRs each)
+constexpr int kMaxSchedGroups = 2048;  // (sequence, KV group) pairs the balanced schedule scans in LDS
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+// 128-bit streaming load: V rows are read exactly once per step, so they are fetched with the
+// non-temporal hint and do not displace the queries and partial records from the caches.
+__device__ __forceinline__ uint4 load_stream(const uint4* p) {
+  const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
 
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
@@ -59,7 +80,8 @@ __device__ __forceinline__ float wave_sum(float x) {
 __device__ __forceinline__ int clamp_len(int L, int Lmax) { return L < 0 ? 0 : (L > Lmax ? Lmax : L); }
 
 // ------------------------------------------------------------------------------------------
-// Routing probe.  grid = B*H_kv, block = 64.  Lane l owns head-dimension elements 2l, 2l+1.
+// Routing probe.  grid = B*H_kv, block = 64*G: wavefront i owns query head i of the group,
+// lane l owns head-dimension elements 2l, 2l+1.
 // ------------------------------------------------------------------------------------------
 struct ProbeArgs {
   const uint32_t* q;       // bf16 pairs
@@ -72,35 +94,36 @@ struct ProbeArgs {
   float tau[4], len_norm;
 };
 
-__global__ __launch_bounds__(64) void sr_probe_kernel(ProbeArgs a) {
+__global__ __launch_bounds__(1024) void sr_probe_kernel(ProbeArgs a) {
+  __shared__ float cosv[kMaxGroup];
   const int bg = blockIdx.x;
   const int b = bg / a.Hkv, g = bg - b * a.Hkv;
-  const int lane = threadIdx.x;
-  const int L = clamp_len(a.seq_lens[b], a.Lmax);
+  const int lane = threadIdx.x & 63, i = threadIdx.x >> 6;
   const uint32_t kw = a.k[(size_t)bg * a.Lmax * (kD / 2) + lane];   // row 0 of the group's keys
+  const uint32_t qw = a.q[((size_t)b * a.Hq + (size_t)g * a.G + i) * (kD / 2) + lane];
   const float k0 = bf16_lo(kw), k1 = bf16_hi(kw);
-  float kk = wave_sum(k0 * k0 + k1 * k1);
+  const float q0 = bf16_lo(qw), q1 = bf16_hi(qw);
+  const float kk = wave_sum(k0 * k0 + k1 * k1);
+  const float dot = wave_sum(q0 * k0 + q1 * k1);
+  const float qq = wave_sum(q0 * q0 + q1 * q1);
   const float nk = a.k0_norm ? a.k0_norm[bg] : sqrtf(kk);
-  float S = 0.f;
-  for (int i = 0; i < a.G; ++i) {
-    const uint32_t qw = a.q[((size_t)b * a.Hq + (size_t)g * a.G + i) * (kD / 2) + lane];
-    const float q0 = bf16_lo(qw), q1 = bf16_hi(qw);
-    const float dot = wave_sum(q0 * k0 + q1 * k1);
-    const float qq = wave_sum(q0 * q0 + q1 * q1);
-    const float den = sqrtf(qq) * nk;
-    S += (den > 0.f) ? dot / den : 0.f;
-  }
-  S /= (float)a.G;
-  const float x = a.len_norm > 0.f ? (float)L / a.len_norm : 0.f;
-  const float tau = ((a.tau[0] * x + a.tau[1]) * x + a.tau[2]) * x + a.tau[3];
-  if (lane == 0) {
+  const float den = sqrtf(qq) * nk;
+  if (lane == 0) cosv[i] = (den > 0.f) ? dot / den : 0.f;           // Eq. 8
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const int L = clamp_len(a.seq_lens[b], a.Lmax);
+    float S = 0.f;
+    for (int j = 0; j < a.G; ++j) S += cosv[j];
+    S /= (float)a.G;                                                // Eq. 9
+    const float x = a.len_norm > 0.f ? (float)L / a.len_norm : 0.f;
+    const float tau = ((a.tau[0] * x + a.tau[1]) * x + a.tau[2]) * x + a.tau[3];
     if (a.group_score) a.group_score[bg] = S;
-    a.mask[bg] = (a.routing && L > 0 && S > tau) ? 1 : 0;
+    a.mask[bg] = (a.routing && L > 0 && S > tau) ? 1 : 0;           // Eq. 10, strict
   }
 }
 
 // ------------------------------------------------------------------------------------------
-// Split-K partial.  grid = (num_splits, B*H_kv), block = 256 (4 wavefronts).
+// Split-K partial attention.
 // ------------------------------------------------------------------------------------------
 struct PartialArgs {
   const uint16_t* q;
@@ -108,37 +131,37 @@ struct PartialArgs {
   const uint16_t* v;
   const int32_t* seq_lens;
   const uint8_t* mask;
-  float* part_o;    // [B,Hq,S,D]  sum_t 2^(z_t - m) v_t
-  float* part_ml;   // [B,Hq,S,2]  m (log2 domain), l
-  int Hq, Hkv, G, Lmax, chunk, S;
-  float scale_log2;  // softmax scale * log2(e)
+  float* part_o;    // [B*Hq, slots, D]  sum_t 2^(z_t - m) v_t
+  float* part_ml;   // [B*Hq, slots, 2]  m (log2 domain), l
+  int32_t* sched;   // balanced schedule only: U, c, start[0..NG]
+  int Hq, Hkv, G, Lmax, NG;
+  int chunk;        // fixed schedule: tokens per chunk
+  int slots;        // partial records per head
+  float scale_log2; // softmax scale * log2(e)
 };
 
 // K tile T, step j: lane (r16, kg) holds token tok0+16T+r16, elements (4j+kg)*8 .. +8.
 // Rows are clamped to the last valid one, so a ragged tail never reads beyond seq_len.
-__device__ __forceinline__ void load_k_block(uint4 (&kr)[4][4], const uint4* __restrict__ K4, int tok0,
-                                             int r16, int kg, int last) {
+// A row reaches the wavefront as 64-byte pieces, two loads per 128-byte line, so these stay
+// ordinary cached loads (the second piece of a line hits); a non-temporal hint here costs bandwidth.
+__device__ __forceinline__ void load_k_tile(uint4 (&kr)[4], const uint4* __restrict__ K4, int tok0, int T,
+                                            int r16, int kg, int last) {
+  int row = tok0 + 16 * T + r16;
+  row = row < last ? row : last;
+  const uint4* p = K4 + (size_t)row * 16 + kg;
 #pragma unroll
-  for (int T = 0; T < 4; ++T) {
-    int row = tok0 + 16 * T + r16;
-    row = row < last ? row : last;
-    const uint4* p = K4 + (size_t)row * 16 + kg;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) kr[T][j] = p[4 * j];
-  }
+  for (int j = 0; j < 4; ++j) kr[j] = p[4 * j];
 }
 
-// V tile T, row r: lane (r16, kg) holds token tok0+16T+4kg+r, elements 8*r16 .. +8.
-__device__ __forceinline__ void load_v_block(uint4 (&vr)[4][4], const uint4* __restrict__ V4, int tok0,
-                                             int r16, int kg, int last) {
+// V tile T, row r: lane (r16, kg) holds token tok0+16T+4kg+r, elements 8*r16 .. +8: each load
+// instruction covers four whole 256-byte rows.
+__device__ __forceinline__ void load_v_tile(uint4 (&vr)[4], const uint4* __restrict__ V4, int tok0, int T,
+                                            int r16, int kg, int last) {
 #pragma unroll
-  for (int T = 0; T < 4; ++T) {
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      int row = tok0 + 16 * T + 4 * kg + r;
-      row = row < last ? row : last;
-      vr[T][r] = V4[(size_t)row * 16 + r16];
-    }
+  for (int r = 0; r < 4; ++r) {
+    int row = tok0 + 16 * T + 4 * kg + r;
+    row = row < last ? row : last;
+    vr[r] = load_stream(V4 + (size_t)row * 16 + r16);
   }
 }
 
@@ -149,8 +172,10 @@ struct WaveState {
 };
 
 // One 64-token block: scores, online softmax, P.V.  With kPrefetch the loads of the block at
-// `next` are issued as soon as the registers they overwrite have been consumed, so the loop
-// body has no conditional loads and the wait counts the compiler inserts stay exact.
+// `next` are issued tile by tile, each as soon as the registers it overwrites have been consumed,
+// so the loop body has no conditional loads and the wait counts the compiler inserts stay exact.
+// The scheduling barriers keep the compiler from hoisting a prefetch above the MFMAs that still
+// read its registers (it would need a second register set) or sinking it to the end of the block.
 template <bool kPrefetch>
 __device__ __forceinline__ void block_step(WaveState& w, uint4 (&kr)[4][4], uint4 (&vr)[4][4], const bf16x8 (&qb)[4],
                                            const uint4* __restrict__ K4, const uint4* __restrict__ V4,
@@ -164,12 +189,20 @@ __device__ __forceinline__ void block_step(WaveState& w, uint4 (&kr)[4][4], uint
 #pragma unroll
     for (int j = 0; j < 4; ++j)
       sc[T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kr[T][j]), qb[j], sc[T], 0, 0, 0);
+#if SR_FINE_PREFETCH
+    __builtin_amdgcn_sched_barrier(0);
+    if (kPrefetch) load_k_tile(kr[T], K4, next, T, r16, kg, last);
+    __builtin_amdgcn_sched_barrier(0);
+#endif
   }
-  // The scheduler must not hoist the prefetch above the MFMAs that still read these registers
-  // (it would need a second register set) nor sink it below the softmax.
+#if !SR_FINE_PREFETCH
   __builtin_amdgcn_sched_barrier(0);
-  if (kPrefetch) load_k_block(kr, K4, next, r16, kg, last);
+  if (kPrefetch) {
+#pragma unroll
+    for (int T = 0; T < 4; ++T) load_k_tile(kr[T], K4, next, T, r16, kg, last);
+  }
   __builtin_amdgcn_sched_barrier(0);
+#endif
   // ---- online softmax over the block
   float bm = -INFINITY;
 #pragma unroll
@@ -201,7 +234,7 @@ __device__ __forceinline__ void block_step(WaveState& w, uint4 (&kr)[4][4], uint
   for (int e = 0; e < 8; ++e) w.acc[e] *= alpha;
   // ---- O^T += V^T P^T : A = V^T (row = dim column r16, k = lane group), B = P^T
 #pragma unroll
-  for (int T = 0; T < 4; ++T)
+  for (int T = 0; T < 4; ++T) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       const uint4 x = vr[T][r];
@@ -215,25 +248,34 @@ __device__ __forceinline__ void block_step(WaveState& w, uint4 (&kr)[4][4], uint
       w.acc[6] = __builtin_amdgcn_mfma_f32_16x16x4f32(bf16_lo(x.w), p, w.acc[6], 0, 0, 0);
       w.acc[7] = __builtin_amdgcn_mfma_f32_16x16x4f32(bf16_hi(x.w), p, w.acc[7], 0, 0, 0);
     }
+#if SR_FINE_PREFETCH
+    __builtin_amdgcn_sched_barrier(0);
+    if (kPrefetch) load_v_tile(vr[T], V4, next, T, r16, kg, last);
+    __builtin_amdgcn_sched_barrier(0);
+#endif
+  }
+#if !SR_FINE_PREFETCH
   __builtin_amdgcn_sched_barrier(0);
-  if (kPrefetch) load_v_block(vr, V4, next, r16, kg, last);
+  if (kPrefetch) {
+#pragma unroll
+    for (int T = 0; T < 4; ++T) load_v_tile(vr[T], V4, next, T, r16, kg, last);
+  }
   __builtin_amdgcn_sched_barrier(0);
+#endif
 }
 
-__global__ __launch_bounds__(256, 2) void sr_partial_kernel(PartialArgs a) {
-  const int s = blockIdx.x;
-  const int bg = blockIdx.y;
-  if (a.mask[bg]) return;                       // Sink Group: no K/V row is touched
-  const int b = bg / a.Hkv, g = bg - b * a.Hkv;
-  const int L = clamp_len(a.seq_lens[b], a.Lmax);
-  const int t_begin = s * a.chunk;
-  if (t_begin >= L) return;                     // chunk lies beyond this sequence
-  const int t_end = min(t_begin + a.chunk, L);
-  const int last = L - 1;
-
+// Attention of the G heads of group (b, g) over tokens [t_begin, t_end) (t_begin a multiple of 64,
+// t_begin < t_end <= L), by the whole workgroup; writes partial record `slot` of each head.
+// Every thread of the workgroup must call it (it synchronises).
+__device__ __forceinline__ void attend_range(const PartialArgs& a, int b, int g, int L, int t_begin, int t_end, int slot) {
+  __shared__ float lds_o[kWaves][kMaxGroup][kOStride];
+  __shared__ float lds_m[kWaves][kMaxGroup];
+  __shared__ float lds_l[kWaves][kMaxGroup];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r16 = lane & 15, kg = lane >> 4;
   const int G = a.G;
+  const int bg = b * a.Hkv + g;
+  const int last = L - 1;
 
   // B operand of Q.K^T: column r16 = query head (zero beyond the group), same k slots as K.
   bf16x8 qb[4];
@@ -256,11 +298,13 @@ __global__ __launch_bounds__(256, 2) void sr_partial_kernel(PartialArgs a) {
 #pragma unroll
   for (int e = 0; e < 8; ++e) w.acc[e] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  int tok0 = t_begin + wave * kBlock;
+  int tok0 = t_begin + wave * kBlock;      // the 4 wavefronts interleave 64-token blocks
   if (tok0 < t_end) {
     uint4 kr[4][4], vr[4][4];
-    load_k_block(kr, K4, tok0, r16, kg, last);
-    load_v_block(vr, V4, tok0, r16, kg, last);
+#pragma unroll
+    for (int T = 0; T < 4; ++T) load_k_tile(kr[T], K4, tok0, T, r16, kg, last);
+#pragma unroll
+    for (int T = 0; T < 4; ++T) load_v_tile(vr[T], V4, tok0, T, r16, kg, last);
     int next = tok0 + kWaves * kBlock;
     while (next < t_end) {
       block_step<true>(w, kr, vr, qb, K4, V4, tok0, next, t_end, last, r16, kg, a.scale_log2);
@@ -269,95 +313,178 @@ __global__ __launch_bounds__(256, 2) void sr_partial_kernel(PartialArgs a) {
     }
     block_step<false>(w, kr, vr, qb, K4, V4, tok0, next, t_end, last, r16, kg, a.scale_log2);
   }
-  float m_run = w.m_run, l_run = w.l_run;
-  f32x4 (&acc)[8] = w.acc;
 
   // ---- merge the 4 wavefronts through LDS, write one partial per head
-  __shared__ float lds_o[kWaves][kMaxGroup][kOStride];
-  __shared__ float lds_m[kWaves][kMaxGroup];
-  __shared__ float lds_l[kWaves][kMaxGroup];
+  float l_run = w.l_run;
   l_run += __shfl_xor(l_run, 16, 64);
   l_run += __shfl_xor(l_run, 32, 64);
   if (r16 < G) {
     float* row = &lds_o[wave][r16][32 * kg];
 #pragma unroll
     for (int vv = 0; vv < 4; ++vv) {
-      *reinterpret_cast<float4*>(row + 8 * vv) = make_float4(acc[0][vv], acc[1][vv], acc[2][vv], acc[3][vv]);
-      *reinterpret_cast<float4*>(row + 8 * vv + 4) = make_float4(acc[4][vv], acc[5][vv], acc[6][vv], acc[7][vv]);
+      *reinterpret_cast<float4*>(row + 8 * vv) = make_float4(w.acc[0][vv], w.acc[1][vv], w.acc[2][vv], w.acc[3][vv]);
+      *reinterpret_cast<float4*>(row + 8 * vv + 4) = make_float4(w.acc[4][vv], w.acc[5][vv], w.acc[6][vv], w.acc[7][vv]);
     }
-    if (kg == 0) { lds_m[wave][r16] = m_run; lds_l[wave][r16] = l_run; }
+    if (kg == 0) { lds_m[wave][r16] = w.m_run; lds_l[wave][r16] = l_run; }
   }
   __syncthreads();
   const int c4 = threadIdx.x & 31;            // float4 column
   for (int h = threadIdx.x >> 5; h < G; h += 8) {
     float M = lds_m[0][h];
 #pragma unroll
-    for (int w = 1; w < kWaves; ++w) M = fmaxf(M, lds_m[w][h]);
+    for (int u = 1; u < kWaves; ++u) M = fmaxf(M, lds_m[u][h]);
     float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
     float l = 0.f;
 #pragma unroll
-    for (int w = 0; w < kWaves; ++w) {
-      const float wt = __builtin_amdgcn_exp2f(lds_m[w][h] - M);   // wave 0 always holds a block, so M is finite
-      const float4 x = *reinterpret_cast<const float4*>(&lds_o[w][h][4 * c4]);
+    for (int u = 0; u < kWaves; ++u) {
+      const float wt = __builtin_amdgcn_exp2f(lds_m[u][h] - M);   // wave 0 always holds a block, so M is finite
+      const float4 x = *reinterpret_cast<const float4*>(&lds_o[u][h][4 * c4]);
       o.x += wt * x.x; o.y += wt * x.y; o.z += wt * x.z; o.w += wt * x.w;
-      l += wt * lds_l[w][h];
+      l += wt * lds_l[u][h];
     }
-    const size_t slot = ((size_t)b * a.Hq + (size_t)g * G + h) * a.S + s;
-    *reinterpret_cast<float4*>(a.part_o + slot * kD + 4 * c4) = o;
-    if (c4 == 0) *reinterpret_cast<float2*>(a.part_ml + slot * 2) = make_float2(M, l);
+    const size_t rec = ((size_t)b * a.Hq + (size_t)g * G + h) * a.slots + slot;
+    *reinterpret_cast<float4*>(a.part_o + rec * kD + 4 * c4) = o;
+    if (c4 == 0) *reinterpret_cast<float2*>(a.part_ml + rec * 2) = make_float2(M, l);
+  }
+}
+
+// Fixed schedule.  grid = (num_splits, B*H_kv), block = 256.
+__global__ __launch_bounds__(256, 2) void sr_partial_fixed_kernel(PartialArgs a) {
+  const int s = blockIdx.x;
+  const int bg = blockIdx.y;
+  if (a.mask[bg]) return;                       // Sink Group: no K/V row is touched
+  const int b = bg / a.Hkv, g = bg - b * a.Hkv;
+  const int L = clamp_len(a.seq_lens[b], a.Lmax);
+  const int t_begin = s * a.chunk;
+  if (t_begin >= L) return;                     // chunk lies beyond this sequence
+  attend_range(a, b, g, L, t_begin, min(t_begin + a.chunk, L), s);
+}
+
+// Balanced schedule.  grid = kBalancedGrid, block = 256.  Unit = one 64-token block of an Active
+// Group; units are numbered group after group; workgroup p owns units [p*c, (p+1)*c), c = ceil(U/P).
+// Partial record j of a group belongs to workgroup (start/c + j).  Workgroup 0 leaves the schedule
+// (U, c, start[]) in `sched` for the merge kernel.
+__global__ __launch_bounds__(256, 2) void sr_partial_balanced_kernel(PartialArgs a) {
+  __shared__ int start[kMaxSchedGroups + 1];
+  __shared__ int wsum[kWaves];
+  __shared__ int first_group;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int NG = a.NG;
+  int carry = 0;
+  for (int base = 0; base < NG; base += 256) {
+    const int i = base + tid;
+    int u = 0;
+    if (i < NG && !a.mask[i]) u = (clamp_len(a.seq_lens[i / a.Hkv], a.Lmax) + kBlock - 1) / kBlock;
+    int x = u;                                   // inclusive scan inside the wavefront
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int y = __shfl_up(x, o, 64);
+      if (lane >= o) x += y;
+    }
+    if (lane == 63) wsum[wave] = x;
+    __syncthreads();
+    int woff = 0;
+#pragma unroll
+    for (int u2 = 0; u2 < kWaves; ++u2) if (u2 < wave) woff += wsum[u2];
+    const int tot = wsum[0] + wsum[1] + wsum[2] + wsum[3];
+    if (i < NG) start[i] = carry + woff + x - u;
+    carry += tot;
+    __syncthreads();
+  }
+  const int U = carry;
+  if (tid == 0) start[NG] = U;
+  const int P = gridDim.x, p = blockIdx.x;
+  const int c = (U + P - 1) / P;
+  __syncthreads();
+  if (p == 0) {
+    if (tid == 0) { a.sched[0] = U; a.sched[1] = c; }
+    for (int i = tid; i <= NG; i += 256) a.sched[2 + i] = start[i];
+  }
+  const int u_lo = p * c, u_hi = min(u_lo + c, U);
+  if (u_lo >= u_hi) return;
+  for (int i = tid; i < NG; i += 256)
+    if (start[i] <= u_lo && u_lo < start[i + 1]) first_group = i;   // exactly one group holds u_lo
+  __syncthreads();
+  for (int i = first_group; i < NG && start[i] < u_hi; ++i) {
+    const int s0 = start[i], s1 = start[i + 1];
+    if (s1 == s0) continue;                     // Sink Group or empty sequence
+    const int b = i / a.Hkv, g = i - b * a.Hkv;
+    const int L = clamp_len(a.seq_lens[b], a.Lmax);
+    const int blk_lo = max(u_lo, s0) - s0, blk_hi = min(u_hi, s1) - s0;
+    attend_range(a, b, g, L, blk_lo * kBlock, min(blk_hi * kBlock, L), p - s0 / c);
+    __syncthreads();                            // LDS of attend_range is reused by the next segment
   }
 }
 
 // ------------------------------------------------------------------------------------------
-// Merge of the chunks.  grid = B*H_q, block = 1024 (16 wavefronts; lane owns 2 columns).
+// Merge of the partials.  grid = B*H_q, block = 1024 (16 wavefronts; lane owns 2 columns).
 // ------------------------------------------------------------------------------------------
 struct CombineArgs {
   const float* part_o;
   const float* part_ml;
   const int32_t* seq_lens;
   const uint8_t* mask;
-  uint32_t* out;    // bf16 pairs
-  int Hq, Hkv, G, Lmax, chunk, S;
+  const int32_t* sched;   // balanced schedule, else NULL
+  uint32_t* out;          // bf16 pairs
+  int Hq, Hkv, G, Lmax, chunk, slots;
 };
 
 __global__ __launch_bounds__(kCombineThreads) void sr_combine_kernel(CombineArgs a) {
   constexpr int NW = kCombineThreads / 64;
+  constexpr int UN = 8;
   const int bh = blockIdx.x;
   const int b = bh / a.Hq, h = bh - b * a.Hq, g = h / a.G;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int L = clamp_len(a.seq_lens[b], a.Lmax);
+  const int bg = b * a.Hkv + g;
   uint32_t* orow = a.out + (size_t)bh * (kD / 2);
-  if (a.mask[b * a.Hkv + g] || L == 0) {        // zero surrogate (Eq. 11) / empty sequence
+  int n = 0;                                     // partial records of this head
+  if (!a.mask[bg] && L > 0) {
+    if (a.sched) {
+      const int c = a.sched[1], s0 = a.sched[2 + bg], s1 = a.sched[3 + bg];
+      if (s1 > s0) n = (s1 - 1) / c - s0 / c + 1;
+    } else {
+      n = (L + a.chunk - 1) / a.chunk;
+    }
+  }
+  if (n == 0) {                                  // zero surrogate (Eq. 11) / empty sequence
     if (wave == 0) orow[lane] = 0u;
     return;
   }
-  const int nvalid = (L + a.chunk - 1) / a.chunk;
-  const float2* ml = reinterpret_cast<const float2*>(a.part_ml) + (size_t)bh * a.S;
-  const float2* po = reinterpret_cast<const float2*>(a.part_o) + (size_t)bh * a.S * (kD / 2);
+  const float2* ml = reinterpret_cast<const float2*>(a.part_ml) + (size_t)bh * a.slots;
+  const float2* po = reinterpret_cast<const float2*>(a.part_o) + (size_t)bh * a.slots * (kD / 2);
 
   __shared__ float red_m[NW];
   __shared__ float red_l[NW];
   __shared__ float2 red_o[NW][64];
   float mx = -INFINITY;
-  for (int s = threadIdx.x; s < nvalid; s += kCombineThreads) mx = fmaxf(mx, ml[s].x);
+  for (int s = threadIdx.x; s < n; s += kCombineThreads) mx = fmaxf(mx, ml[s].x);
 #pragma unroll
   for (int o = 32; o >= 1; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
   if (lane == 0) red_m[wave] = mx;
   __syncthreads();
   float M = red_m[0];
 #pragma unroll
-  for (int w = 1; w < NW; ++w) M = fmaxf(M, red_m[w]);
+  for (int u = 1; u < NW; ++u) M = fmaxf(M, red_m[u]);
 
   float2 acc = make_float2(0.f, 0.f);
   float lsum = 0.f;
-#pragma unroll 4
-  for (int s = wave; s < nvalid; s += NW) {
-    const float2 st = ml[s];
-    const float wt = __builtin_amdgcn_exp2f(st.x - M);
-    const float2 o = po[(size_t)s * (kD / 2) + lane];
-    acc.x += wt * o.x;
-    acc.y += wt * o.y;
-    lsum += wt * st.y;
+  for (int s0 = wave; s0 < n; s0 += NW * UN) {   // UN rows in flight per wavefront
+    float2 st[UN], o[UN];
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      const int s = s0 + u * NW;
+      const bool ok = s < n;
+      st[u] = ok ? ml[s] : make_float2(-INFINITY, 0.f);
+      o[u] = ok ? po[(size_t)s * (kD / 2) + lane] : make_float2(0.f, 0.f);
+    }
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      const float wt = __builtin_amdgcn_exp2f(st[u].x - M);
+      acc.x += wt * o[u].x;
+      acc.y += wt * o[u].y;
+      lsum += wt * st[u].y;
+    }
   }
   red_o[wave][lane] = acc;
   if (lane == 0) red_l[wave] = lsum;
@@ -366,7 +493,7 @@ __global__ __launch_bounds__(kCombineThreads) void sr_combine_kernel(CombineArgs
     float2 t = red_o[0][lane];
     float l = red_l[0];
 #pragma unroll
-    for (int w = 1; w < NW; ++w) { t.x += red_o[w][lane].x; t.y += red_o[w][lane].y; l += red_l[w]; }
+    for (int u = 1; u < NW; ++u) { t.x += red_o[u][lane].x; t.y += red_o[u][lane].y; l += red_l[u]; }
     const float inv = 1.0f / l;
     orow[lane] = f32_to_bf16_rne(t.x * inv) | (f32_to_bf16_rne(t.y * inv) << 16);
   }
@@ -406,7 +533,7 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct Layout {
   sr_plan plan;
-  size_t off_o, off_ml, off_score;
+  size_t off_o, off_ml, off_score, off_sched;
 };
 
 int make_layout(const sr_route_params* p, Layout* lay) {
@@ -423,28 +550,42 @@ int make_layout(const sr_route_params* p, Layout* lay) {
   if (G > kMaxGroup) return SR_ERR_UNSUPPORTED;
   if (!(p->sm_scale >= 0.f) || p->sm_scale > 1e30f) return SR_ERR_SHAPE;
 
-  int chunk;
-  if (p->num_splits > 0) {
-    const int per = (p->max_seq_len + p->num_splits - 1) / p->num_splits;
-    chunk = (int)align_up((size_t)per, kChunkUnit);
+  const int NG = p->batch * p->n_kv_heads;
+  const int blocks = (p->max_seq_len + kBlock - 1) / kBlock;
+  sr_plan& pl = lay->plan;
+  pl.group_size = G;
+  if (p->num_splits == 0 && NG <= kMaxSchedGroups && (int64_t)NG * blocks < ((int64_t)1 << 30)) {
+    pl.schedule = 1;
+    pl.chunk_tokens = 0;
+    pl.num_splits = 0;
+    pl.partial_grid = kBalancedGrid;
+    pl.slots_per_head = blocks < kBalancedGrid + 1 ? blocks : kBalancedGrid + 1;
   } else {
-    // Size chunks so that, with about 40% of the groups active (the paper's retained budget,
-    // Section 5.1), roughly 2048 workgroups have work: 8 per compute unit.
-    const double active_tokens = 0.4 * (double)p->batch * p->n_kv_heads * p->max_seq_len;
-    int units = (int)(active_tokens / (2048.0 * kChunkUnit));
-    units = units < 1 ? 1 : (units > 8 ? 8 : units);
-    chunk = units * kChunkUnit;
+    int chunk;
+    if (p->num_splits > 0) {
+      const int per = (p->max_seq_len + p->num_splits - 1) / p->num_splits;
+      chunk = (int)align_up((size_t)per, kChunkUnit);
+    } else {
+      // too many groups to schedule in LDS: plain chunks sized so that, with about 40% of the
+      // groups active (the paper's retained budget, Section 5.1), some 2048 workgroups have work
+      const double active_tokens = 0.4 * (double)NG * p->max_seq_len;
+      int units = (int)(active_tokens / (2048.0 * kChunkUnit));
+      units = units < 1 ? 1 : (units > 8 ? 8 : units);
+      chunk = units * kChunkUnit;
+    }
+    pl.schedule = 0;
+    pl.chunk_tokens = chunk;
+    pl.num_splits = (p->max_seq_len + chunk - 1) / chunk;
+    pl.partial_grid = pl.num_splits * NG;
+    pl.slots_per_head = pl.num_splits;
   }
-  const int S = (p->max_seq_len + chunk - 1) / chunk;
-  lay->plan.chunk_tokens = chunk;
-  lay->plan.num_splits = S;
-  lay->plan.group_size = G;
-  lay->plan.partial_grid = S * p->batch * p->n_kv_heads;
   const size_t heads = (size_t)p->batch * p->n_q_heads;
+  const size_t S = (size_t)pl.slots_per_head;
   lay->off_o = 0;
   lay->off_ml = align_up(heads * S * kD * sizeof(float), 256);
   lay->off_score = lay->off_ml + align_up(heads * S * 2 * sizeof(float), 256);
-  lay->plan.workspace_bytes = lay->off_score + align_up((size_t)p->batch * p->n_kv_heads * sizeof(float), 256);
+  lay->off_sched = lay->off_score + align_up((size_t)NG * sizeof(float), 256);
+  pl.workspace_bytes = lay->off_sched + align_up((size_t)(NG + 3) * sizeof(int32_t), 256);
   return SR_OK;
 }
 
@@ -463,7 +604,7 @@ int launch_probe(const void* q, const void* k, const int32_t* seq_lens, const sr
   a.routing = p->routing_enabled != 0;
   for (int i = 0; i < 4; ++i) a.tau[i] = p->tau_coef[i];
   a.len_norm = p->len_norm;
-  hipLaunchKernelGGL(sr_probe_kernel, dim3(p->batch * p->n_kv_heads), dim3(64), 0, st, a);
+  hipLaunchKernelGGL(sr_probe_kernel, dim3(p->batch * p->n_kv_heads), dim3(64 * lay.plan.group_size), 0, st, a);
   return hipGetLastError() == hipSuccess ? SR_OK : SR_ERR_HIP;
 }
 
@@ -482,6 +623,8 @@ int decode_impl(const void* q, const void* k, const void* v, const int32_t* seq_
   float* part_o = reinterpret_cast<float*>(ws + lay.off_o);
   float* part_ml = reinterpret_cast<float*>(ws + lay.off_ml);
   float* score = reinterpret_cast<float*>(ws + lay.off_score);
+  int32_t* sched = reinterpret_cast<int32_t*>(ws + lay.off_sched);
+  const bool balanced = lay.plan.schedule == 1;
 
   hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
   if (stage_us) {
@@ -500,21 +643,26 @@ int decode_impl(const void* q, const void* k, const void* v, const int32_t* seq_
     a.q = static_cast<const uint16_t*>(q);
     a.k = static_cast<const uint16_t*>(k);
     a.v = static_cast<const uint16_t*>(v);
-    a.seq_lens = seq_lens; a.mask = mask; a.part_o = part_o; a.part_ml = part_ml;
+    a.seq_lens = seq_lens; a.mask = mask; a.part_o = part_o; a.part_ml = part_ml; a.sched = sched;
     a.Hq = p->n_q_heads; a.Hkv = p->n_kv_heads; a.G = lay.plan.group_size; a.Lmax = p->max_seq_len;
-    a.chunk = lay.plan.chunk_tokens; a.S = lay.plan.num_splits;
+    a.NG = p->batch * p->n_kv_heads;
+    a.chunk = lay.plan.chunk_tokens; a.slots = lay.plan.slots_per_head;
     const float scale = p->sm_scale > 0.f ? p->sm_scale : 0.08838834764831845f;   // 1/sqrt(128)
     a.scale_log2 = scale * 1.4426950408889634f;
-    hipLaunchKernelGGL(sr_partial_kernel, dim3(lay.plan.num_splits, p->batch * p->n_kv_heads), dim3(64 * kWaves), 0, st, a);
+    if (balanced)
+      hipLaunchKernelGGL(sr_partial_balanced_kernel, dim3(kBalancedGrid), dim3(64 * kWaves), 0, st, a);
+    else
+      hipLaunchKernelGGL(sr_partial_fixed_kernel, dim3(lay.plan.num_splits, a.NG), dim3(64 * kWaves), 0, st, a);
     ok = hipGetLastError() == hipSuccess;
   }
   if (ok) ok = mark(2);
   if (ok) {
     CombineArgs c;
     c.part_o = part_o; c.part_ml = part_ml; c.seq_lens = seq_lens; c.mask = mask;
+    c.sched = balanced ? sched : nullptr;
     c.out = static_cast<uint32_t*>(out);
     c.Hq = p->n_q_heads; c.Hkv = p->n_kv_heads; c.G = lay.plan.group_size; c.Lmax = p->max_seq_len;
-    c.chunk = lay.plan.chunk_tokens; c.S = lay.plan.num_splits;
+    c.chunk = lay.plan.chunk_tokens; c.slots = lay.plan.slots_per_head;
     hipLaunchKernelGGL(sr_combine_kernel, dim3(p->batch * p->n_q_heads), dim3(kCombineThreads), 0, st, c);
     ok = hipGetLastError() == hipSuccess;
   }

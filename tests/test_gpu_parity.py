@@ -23,7 +23,9 @@ def _check(sb, taus=None, label="", **kw):
                             routing_enabled=kw.get("routing_enabled", True))
         rep = gu.compare(res, ref, G, "%s tau=%.4f" % (label, tau))
         reports.append(rep)
-        print(label, "tau=%.4f" % tau, rep, "splits", res["plan"].num_splits, "chunk", res["plan"].chunk_tokens, flush=True)
+        pl = res["plan"]
+        print(label, "tau=%.4f" % tau, rep, "schedule", pl.schedule, "grid", pl.partial_grid, "splits", pl.num_splits,
+              "chunk", pl.chunk_tokens, flush=True)
     return reports
 
 
@@ -125,3 +127,4 @@ def test_full_size(name):
     print(name, "generated", sb.k.nbytes * 2 / 1e6, "MB", flush=True)
     _check(sb, label=name + "-full")
     _check(sb, taus=[0.55], label=name + "-full-dense", routing_enabled=False)
+    _check(sb, taus=[0.55], label=name + "-full-fixed-chunks", num_splits=200)
