@@ -23,10 +23,9 @@
 //   sr_combine_kernel  log-sum-exp merge of the partials, bf16 output; zeros for Sink Groups
 //                      (Eq. 11).
 //
-// Register layouts of the two MFMA shapes used (lane = 0..63, r16 = lane % 16, kg = lane / 16):
+// Register layout of the MFMA shape used for both products (lane = 0..63, r16 = lane % 16, kg = lane / 16):
 //   v_mfma_f32_16x16x32_bf16  A: row r16, 8 consecutive k of k-group kg; B: column r16, same k;
 //                             D: column r16, rows 4*kg + {0,1,2,3} in the 4 result registers.
-//   v_mfma_f32_16x16x4_f32    A: row r16, k = kg; B: column r16, k = kg; D as above.
 // Only "A row = lane%16, B column = lane%16, both operands use the same k slot" is relied on,
 // so any consistent assignment of head-dimension elements to k slots gives the right dot product.
 #include <hip/hip_runtime.h>
@@ -36,6 +35,9 @@
 
 #ifndef SR_FINE_PREFETCH
 #define SR_FINE_PREFETCH 1
+#endif
+#ifndef SR_P_SPLIT
+#define SR_P_SPLIT 1      // softmax weights enter the P.V MFMA as bf16 hi + bf16 lo (1) or bf16 only (0)
 #endif
 
 namespace {
@@ -49,6 +51,7 @@ constexpr int kOStride = kD + 4;     // LDS row stride (floats) of the per-wave 
 constexpr int kCombineThreads = 1024;
 constexpr int kBalancedGrid = 512;   // 256 compute units x 2 resident workgroups (228 VGPRs each)
 constexpr int kMaxSchedGroups = 2048;  // (sequence, KV group) pairs the balanced schedule scans in LDS
+constexpr int kMaxFusedHeads = 512;    // query heads (all sequences) the balanced kernel probes itself
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -71,54 +74,80 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
   return u >> 16;
 }
 
-__device__ __forceinline__ float wave_sum(float x) {
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o, 64);
-  return x;
-}
-
 __device__ __forceinline__ int clamp_len(int L, int Lmax) { return L < 0 ? 0 : (L > Lmax ? Lmax : L); }
 
 // ------------------------------------------------------------------------------------------
-// Routing probe.  grid = B*H_kv, block = 64*G: wavefront i owns query head i of the group,
-// lane l owns head-dimension elements 2l, 2l+1.
+// Routing signal (Section 4.2).  Sixteen lanes share one query head, lane16 owns head-dimension
+// elements 8*lane16 .. +8.  The standalone probe kernel and the probe fused into the balanced
+// partial kernel run exactly this arithmetic, in this order, so their decisions are identical.
 // ------------------------------------------------------------------------------------------
+struct RouteRule {
+  float tau[4], len_norm;
+  int routing;
+};
+
+// Eq. 8 for one head; qw / kw are this lane's 8 elements of the query and of K_0.
+// anchor_norm < 0 means "recompute ||K_0||".  All 16 lanes of the head must be active.
+__device__ __forceinline__ float head_cosine(const uint4 qw, const uint4 kw, float anchor_norm) {
+  const uint32_t qs[4] = {qw.x, qw.y, qw.z, qw.w}, ks[4] = {kw.x, kw.y, kw.z, kw.w};
+  float dot = 0.f, qq = 0.f, kk = 0.f;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const float q0 = bf16_lo(qs[e]), q1 = bf16_hi(qs[e]), k0 = bf16_lo(ks[e]), k1 = bf16_hi(ks[e]);
+    dot = fmaf(q0, k0, dot); dot = fmaf(q1, k1, dot);
+    qq = fmaf(q0, q0, qq);   qq = fmaf(q1, q1, qq);
+    kk = fmaf(k0, k0, kk);   kk = fmaf(k1, k1, kk);
+  }
+#pragma unroll
+  for (int o = 8; o >= 1; o >>= 1) {
+    dot += __shfl_xor(dot, o, 16);
+    qq += __shfl_xor(qq, o, 16);
+    kk += __shfl_xor(kk, o, 16);
+  }
+  const float nk = anchor_norm >= 0.f ? anchor_norm : sqrtf(kk);
+  const float den = sqrtf(qq) * nk;
+  return (den > 0.f) ? dot / den : 0.f;
+}
+
+// Eq. 9-10 and the cubic threshold of Appendix A.  cosines: the G values of the group, in head order.
+__device__ __forceinline__ bool route_decide(const float* cosines, int G, int L, const RouteRule& r, float* S_out) {
+  float S = 0.f;
+  for (int j = 0; j < G; ++j) S += cosines[j];
+  S /= (float)G;
+  const float x = r.len_norm > 0.f ? (float)L / r.len_norm : 0.f;
+  const float tau = ((r.tau[0] * x + r.tau[1]) * x + r.tau[2]) * x + r.tau[3];
+  *S_out = S;
+  return r.routing && L > 0 && S > tau;       // strict; NaN compares false, so the group stays active
+}
+
+// Standalone probe.  grid = B*H_kv, block = 256: 16 lanes per head, up to 16 heads.
 struct ProbeArgs {
-  const uint32_t* q;       // bf16 pairs
-  const uint32_t* k;
+  const uint4* q;
+  const uint4* k;
   const int32_t* seq_lens;
   const float* k0_norm;    // optional
   float* group_score;      // optional
   uint8_t* mask;
-  int Hq, Hkv, G, Lmax, routing;
-  float tau[4], len_norm;
+  int Hq, Hkv, G, Lmax;
+  RouteRule rule;
 };
 
-__global__ __launch_bounds__(1024) void sr_probe_kernel(ProbeArgs a) {
+__global__ __launch_bounds__(256) void sr_probe_kernel(ProbeArgs a) {
   __shared__ float cosv[kMaxGroup];
   const int bg = blockIdx.x;
   const int b = bg / a.Hkv, g = bg - b * a.Hkv;
-  const int lane = threadIdx.x & 63, i = threadIdx.x >> 6;
-  const uint32_t kw = a.k[(size_t)bg * a.Lmax * (kD / 2) + lane];   // row 0 of the group's keys
-  const uint32_t qw = a.q[((size_t)b * a.Hq + (size_t)g * a.G + i) * (kD / 2) + lane];
-  const float k0 = bf16_lo(kw), k1 = bf16_hi(kw);
-  const float q0 = bf16_lo(qw), q1 = bf16_hi(qw);
-  const float kk = wave_sum(k0 * k0 + k1 * k1);
-  const float dot = wave_sum(q0 * k0 + q1 * k1);
-  const float qq = wave_sum(q0 * q0 + q1 * q1);
-  const float nk = a.k0_norm ? a.k0_norm[bg] : sqrtf(kk);
-  const float den = sqrtf(qq) * nk;
-  if (lane == 0) cosv[i] = (den > 0.f) ? dot / den : 0.f;           // Eq. 8
+  const int lane16 = threadIdx.x & 15, i = threadIdx.x >> 4;
+  const int hd = i < a.G ? i : 0;
+  const uint4 kw = a.k[(size_t)bg * a.Lmax * (kD / 8) + lane16];          // row 0 of the group's keys
+  const uint4 qw = a.q[((size_t)b * a.Hq + (size_t)g * a.G + hd) * (kD / 8) + lane16];
+  const float c = head_cosine(qw, kw, a.k0_norm ? a.k0_norm[bg] : -1.f);
+  if (lane16 == 0 && i < a.G) cosv[i] = c;
   __syncthreads();
   if (threadIdx.x == 0) {
-    const int L = clamp_len(a.seq_lens[b], a.Lmax);
-    float S = 0.f;
-    for (int j = 0; j < a.G; ++j) S += cosv[j];
-    S /= (float)a.G;                                                // Eq. 9
-    const float x = a.len_norm > 0.f ? (float)L / a.len_norm : 0.f;
-    const float tau = ((a.tau[0] * x + a.tau[1]) * x + a.tau[2]) * x + a.tau[3];
+    float S;
+    const bool skip = route_decide(cosv, a.G, clamp_len(a.seq_lens[b], a.Lmax), a.rule, &S);
     if (a.group_score) a.group_score[bg] = S;
-    a.mask[bg] = (a.routing && L > 0 && S > tau) ? 1 : 0;           // Eq. 10, strict
+    a.mask[bg] = skip ? 1 : 0;
   }
 }
 
@@ -130,7 +159,10 @@ struct PartialArgs {
   const uint16_t* k;
   const uint16_t* v;
   const int32_t* seq_lens;
-  const uint8_t* mask;
+  uint8_t* mask;    // [B*Hkv] read (written first when the probe is fused)
+  const float* k0_norm;   // fused probe: optional cached ||K_0||
+  float* group_score;     // fused probe: S_g out
+  RouteRule rule;         // fused probe
   float* part_o;    // [B*Hq, slots, D]  sum_t 2^(z_t - m) v_t
   float* part_ml;   // [B*Hq, slots, 2]  m (log2 domain), l
   int32_t* sched;   // balanced schedule only: U, c, start[0..NG]
@@ -232,25 +264,51 @@ __device__ __forceinline__ void block_step(WaveState& w, uint4 (&kr)[4][4], uint
   w.m_run = m_new;
 #pragma unroll
   for (int e = 0; e < 8; ++e) w.acc[e] *= alpha;
-  // ---- O^T += V^T P^T : A = V^T (row = dim column r16, k = lane group), B = P^T
+  // ---- O^T += V^T P^T on the bf16 matrix cores, two 16-token tiles per MFMA (k = 32).
+  // A = V^T: row = this lane's 16-byte column chunk r16, and the lane's k slots are the 8 tokens it
+  // loaded for tiles T and T+1 (4kg + r each): for one element e of the chunk, v_perm gathers its
+  // 8 token values out of the 8 loaded rows, so V needs no transpose through LDS.
+  // B = P^T: column = head r16, same 8 tokens - the lane's own probabilities.  P enters as bf16
+  // hi + bf16 lo (two MFMAs), which keeps ~16 mantissa bits; products accumulate in fp32.
 #pragma unroll
-  for (int T = 0; T < 4; ++T) {
+  for (int T = 0; T < 4; T += 2) {
+    bf16x8 bhi, blo;
+    {
+      float pv[8] = {sc[T][0], sc[T][1], sc[T][2], sc[T][3], sc[T + 1][0], sc[T + 1][1], sc[T + 1][2], sc[T + 1][3]};
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const uint4 x = vr[T][r];
-      const float p = sc[T][r];
-      w.acc[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(bf16_lo(x.x), p, w.acc[0], 0, 0, 0);
-      w.acc[1] = __builtin_amdgcn_mfma_f32_16x16x4f32(bf16_hi(x.x), p, w.acc[1], 0, 0, 0);
-      w.acc[2] = __builtin_amdgcn_mfma_f32_16x16x4f32(bf16_lo(x.y), p, w.acc[2], 0, 0, 0);
-      w.acc[3] = __builtin_amdgcn_mfma_f32_16x16x4f32(bf16_hi(x.y), p, w.acc[3], 0, 0, 0);
-      w.acc[4] = __builtin_amdgcn_mfma_f32_16x16x4f32(bf16_lo(x.z), p, w.acc[4], 0, 0, 0);
-      w.acc[5] = __builtin_amdgcn_mfma_f32_16x16x4f32(bf16_hi(x.z), p, w.acc[5], 0, 0, 0);
-      w.acc[6] = __builtin_amdgcn_mfma_f32_16x16x4f32(bf16_lo(x.w), p, w.acc[6], 0, 0, 0);
-      w.acc[7] = __builtin_amdgcn_mfma_f32_16x16x4f32(bf16_hi(x.w), p, w.acc[7], 0, 0, 0);
+      for (int i = 0; i < 8; ++i) {
+        const __bf16 hv = (__bf16)pv[i];
+        bhi[i] = hv;
+#if SR_P_SPLIT
+        blo[i] = (__bf16)(pv[i] - (float)hv);
+#endif
+      }
+    }
+    const uint32_t wa[4][4] = {{vr[T][0].x, vr[T][0].y, vr[T][0].z, vr[T][0].w}, {vr[T][1].x, vr[T][1].y, vr[T][1].z, vr[T][1].w},
+                               {vr[T][2].x, vr[T][2].y, vr[T][2].z, vr[T][2].w}, {vr[T][3].x, vr[T][3].y, vr[T][3].z, vr[T][3].w}};
+    const uint32_t wb[4][4] = {{vr[T + 1][0].x, vr[T + 1][0].y, vr[T + 1][0].z, vr[T + 1][0].w}, {vr[T + 1][1].x, vr[T + 1][1].y, vr[T + 1][1].z, vr[T + 1][1].w},
+                               {vr[T + 1][2].x, vr[T + 1][2].y, vr[T + 1][2].z, vr[T + 1][2].w}, {vr[T + 1][3].x, vr[T + 1][3].y, vr[T + 1][3].z, vr[T + 1][3].w}};
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {                 // 32-bit word m of the chunk = elements 2m, 2m+1
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {
+        const uint32_t sel = half ? 0x07060302u : 0x05040100u;   // high / low bf16 of both words
+        uint4 av;
+        av.x = __builtin_amdgcn_perm(wa[1][m], wa[0][m], sel);
+        av.y = __builtin_amdgcn_perm(wa[3][m], wa[2][m], sel);
+        av.z = __builtin_amdgcn_perm(wb[1][m], wb[0][m], sel);
+        av.w = __builtin_amdgcn_perm(wb[3][m], wb[2][m], sel);
+        const bf16x8 am = __builtin_bit_cast(bf16x8, av);
+        const int e = 2 * m + half;
+        w.acc[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(am, bhi, w.acc[e], 0, 0, 0);
+#if SR_P_SPLIT
+        w.acc[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(am, blo, w.acc[e], 0, 0, 0);
+#endif
+      }
     }
 #if SR_FINE_PREFETCH
     __builtin_amdgcn_sched_barrier(0);
-    if (kPrefetch) load_v_tile(vr[T], V4, next, T, r16, kg, last);
+    if (kPrefetch) { load_v_tile(vr[T], V4, next, T, r16, kg, last); load_v_tile(vr[T + 1], V4, next, T + 1, r16, kg, last); }
     __builtin_amdgcn_sched_barrier(0);
 #endif
   }
@@ -364,17 +422,62 @@ __global__ __launch_bounds__(256, 2) void sr_partial_fixed_kernel(PartialArgs a)
 // Group; units are numbered group after group; workgroup p owns units [p*c, (p+1)*c), c = ceil(U/P).
 // Partial record j of a group belongs to workgroup (start/c + j).  Workgroup 0 leaves the schedule
 // (U, c, start[]) in `sched` for the merge kernel.
+// With kFused every workgroup first evaluates the routing rule for all groups itself (the queries
+// and anchor rows are a few tens of KB, served by L2), as the paper's kernel does inline, so no
+// separate probe launch precedes it; workgroup 0 writes skip mask and group scores.  Otherwise
+// the mask written by sr_probe_kernel is read.
+template <bool kFused>
 __global__ __launch_bounds__(256, 2) void sr_partial_balanced_kernel(PartialArgs a) {
   __shared__ int start[kMaxSchedGroups + 1];
+  __shared__ int lens[kMaxSchedGroups];
+  __shared__ float cosv[kFused ? kMaxFusedHeads : 1];
   __shared__ int wsum[kWaves];
   __shared__ int first_group;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int NG = a.NG;
+  const int NG = a.NG, G = a.G;
+  const int p = blockIdx.x, P = gridDim.x;
+  for (int i = tid; i < NG; i += 256) lens[i] = clamp_len(a.seq_lens[i / a.Hkv], a.Lmax);
+  if (kFused) {
+    const int NH = NG * G, lane16 = tid & 15;
+    const uint4* q4 = reinterpret_cast<const uint4*>(a.q);
+    const uint4* k4 = reinterpret_cast<const uint4*>(a.k);
+    constexpr int UN = 8;                        // 8 x 16 heads per sweep, all loads in flight at once
+    for (int h0 = 0; h0 < NH; h0 += 16 * UN) {
+      uint4 qw[UN], kw[UN];
+      float kn[UN];
+#pragma unroll
+      for (int u = 0; u < UN; ++u) {
+        int hd = h0 + 16 * u + (tid >> 4);
+        hd = hd < NH ? hd : NH - 1;
+        const int i = hd / G;
+        qw[u] = q4[(size_t)hd * (kD / 8) + lane16];
+        kw[u] = k4[(size_t)i * a.Lmax * (kD / 8) + lane16];
+        kn[u] = a.k0_norm ? a.k0_norm[i] : -1.f;
+      }
+#pragma unroll
+      for (int u = 0; u < UN; ++u) {
+        const int hd = h0 + 16 * u + (tid >> 4);
+        const float cs = head_cosine(qw[u], kw[u], kn[u]);
+        if (lane16 == 0 && hd < NH) cosv[hd] = cs;
+      }
+    }
+  }
+  __syncthreads();
   int carry = 0;
   for (int base = 0; base < NG; base += 256) {
     const int i = base + tid;
     int u = 0;
-    if (i < NG && !a.mask[i]) u = (clamp_len(a.seq_lens[i / a.Hkv], a.Lmax) + kBlock - 1) / kBlock;
+    if (i < NG) {
+      bool skip;
+      if (kFused) {
+        float S;
+        skip = route_decide(cosv + i * G, G, lens[i], a.rule, &S);
+        if (p == 0) { a.mask[i] = skip ? 1 : 0; if (a.group_score) a.group_score[i] = S; }
+      } else {
+        skip = a.mask[i] != 0;
+      }
+      if (!skip) u = (lens[i] + kBlock - 1) / kBlock;
+    }
     int x = u;                                   // inclusive scan inside the wavefront
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) {
@@ -393,7 +496,6 @@ __global__ __launch_bounds__(256, 2) void sr_partial_balanced_kernel(PartialArgs
   }
   const int U = carry;
   if (tid == 0) start[NG] = U;
-  const int P = gridDim.x, p = blockIdx.x;
   const int c = (U + P - 1) / P;
   __syncthreads();
   if (p == 0) {
@@ -409,7 +511,7 @@ __global__ __launch_bounds__(256, 2) void sr_partial_balanced_kernel(PartialArgs
     const int s0 = start[i], s1 = start[i + 1];
     if (s1 == s0) continue;                     // Sink Group or empty sequence
     const int b = i / a.Hkv, g = i - b * a.Hkv;
-    const int L = clamp_len(a.seq_lens[b], a.Lmax);
+    const int L = lens[i];
     const int blk_lo = max(u_lo, s0) - s0, blk_hi = min(u_hi, s1) - s0;
     attend_range(a, b, g, L, blk_lo * kBlock, min(blk_hi * kBlock, L), p - s0 / c);
     __syncthreads();                            // LDS of attend_range is reused by the next segment
@@ -591,20 +693,26 @@ int make_layout(const sr_route_params* p, Layout* lay) {
 
 inline bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
 
+RouteRule make_rule(const sr_route_params* p) {
+  RouteRule r;
+  for (int i = 0; i < 4; ++i) r.tau[i] = p->tau_coef[i];
+  r.len_norm = p->len_norm;
+  r.routing = p->routing_enabled != 0;
+  return r;
+}
+
 int launch_probe(const void* q, const void* k, const int32_t* seq_lens, const sr_route_params* p,
                  const Layout& lay, float* score, uint8_t* mask, hipStream_t st) {
   ProbeArgs a;
-  a.q = static_cast<const uint32_t*>(q);
-  a.k = static_cast<const uint32_t*>(k);
+  a.q = static_cast<const uint4*>(q);
+  a.k = static_cast<const uint4*>(k);
   a.seq_lens = seq_lens;
   a.k0_norm = p->k0_norm;
   a.group_score = score;
   a.mask = mask;
   a.Hq = p->n_q_heads; a.Hkv = p->n_kv_heads; a.G = lay.plan.group_size; a.Lmax = p->max_seq_len;
-  a.routing = p->routing_enabled != 0;
-  for (int i = 0; i < 4; ++i) a.tau[i] = p->tau_coef[i];
-  a.len_norm = p->len_norm;
-  hipLaunchKernelGGL(sr_probe_kernel, dim3(p->batch * p->n_kv_heads), dim3(64 * lay.plan.group_size), 0, st, a);
+  a.rule = make_rule(p);
+  hipLaunchKernelGGL(sr_probe_kernel, dim3(p->batch * p->n_kv_heads), dim3(256), 0, st, a);
   return hipGetLastError() == hipSuccess ? SR_OK : SR_ERR_HIP;
 }
 
@@ -625,6 +733,7 @@ int decode_impl(const void* q, const void* k, const void* v, const int32_t* seq_
   float* score = reinterpret_cast<float*>(ws + lay.off_score);
   int32_t* sched = reinterpret_cast<int32_t*>(ws + lay.off_sched);
   const bool balanced = lay.plan.schedule == 1;
+  const bool fused = balanced && (int64_t)p->batch * p->n_q_heads <= kMaxFusedHeads;
 
   hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
   if (stage_us) {
@@ -636,7 +745,7 @@ int decode_impl(const void* q, const void* k, const void* v, const int32_t* seq_
   }
   auto mark = [&](int i) { return !stage_us || hipEventRecord(ev[i], st) == hipSuccess; };
   bool ok = mark(0);
-  if (ok) ok = launch_probe(q, k, seq_lens, p, lay, score, mask, st) == SR_OK;
+  if (ok && !fused) ok = launch_probe(q, k, seq_lens, p, lay, score, mask, st) == SR_OK;
   if (ok) ok = mark(1);
   if (ok) {
     PartialArgs a;
@@ -644,13 +753,16 @@ int decode_impl(const void* q, const void* k, const void* v, const int32_t* seq_
     a.k = static_cast<const uint16_t*>(k);
     a.v = static_cast<const uint16_t*>(v);
     a.seq_lens = seq_lens; a.mask = mask; a.part_o = part_o; a.part_ml = part_ml; a.sched = sched;
+    a.k0_norm = p->k0_norm; a.group_score = score; a.rule = make_rule(p);
     a.Hq = p->n_q_heads; a.Hkv = p->n_kv_heads; a.G = lay.plan.group_size; a.Lmax = p->max_seq_len;
     a.NG = p->batch * p->n_kv_heads;
     a.chunk = lay.plan.chunk_tokens; a.slots = lay.plan.slots_per_head;
     const float scale = p->sm_scale > 0.f ? p->sm_scale : 0.08838834764831845f;   // 1/sqrt(128)
     a.scale_log2 = scale * 1.4426950408889634f;
-    if (balanced)
-      hipLaunchKernelGGL(sr_partial_balanced_kernel, dim3(kBalancedGrid), dim3(64 * kWaves), 0, st, a);
+    if (fused)
+      hipLaunchKernelGGL(sr_partial_balanced_kernel<true>, dim3(kBalancedGrid), dim3(64 * kWaves), 0, st, a);
+    else if (balanced)
+      hipLaunchKernelGGL(sr_partial_balanced_kernel<false>, dim3(kBalancedGrid), dim3(64 * kWaves), 0, st, a);
     else
       hipLaunchKernelGGL(sr_partial_fixed_kernel, dim3(lay.plan.num_splits, a.NG), dim3(64 * kWaves), 0, st, a);
     ok = hipGetLastError() == hipSuccess;
