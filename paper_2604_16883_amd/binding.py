@@ -13,7 +13,8 @@ import os
 from typing import Optional, Sequence
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libsinkrouter.so")
+# SINKROUTER_LIB selects another build of the same library (kernel tuning experiments)
+LIB_PATH = os.environ.get("SINKROUTER_LIB") or os.path.join(HERE, "libsinkrouter.so")
 
 SR_OK = 0
 SR_ERR_NULL = -1

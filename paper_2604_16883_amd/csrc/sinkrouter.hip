@@ -36,6 +36,14 @@
 #ifndef SR_FINE_PREFETCH
 #define SR_FINE_PREFETCH 1
 #endif
+#ifndef SR_TIMELINE
+#define SR_TIMELINE 0     // 1: debug build, every workgroup leaves 8 wall-clock stamps behind the workspace
+#endif
+#if SR_TIMELINE
+#define SR_STAMP(a, i) do { if (threadIdx.x == 0) (a).timeline[blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
+#else
+#define SR_STAMP(a, i) do { } while (0)
+#endif
 #ifndef SR_P_SPLIT
 #define SR_P_SPLIT 1      // softmax weights enter the P.V MFMA as bf16 hi + bf16 lo (1) or bf16 only (0)
 #endif
@@ -77,33 +85,40 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
 __device__ __forceinline__ int clamp_len(int L, int Lmax) { return L < 0 ? 0 : (L > Lmax ? Lmax : L); }
 
 // ------------------------------------------------------------------------------------------
-// Routing signal (Section 4.2).  Sixteen lanes share one query head, lane16 owns head-dimension
-// elements 8*lane16 .. +8.  The standalone probe kernel and the probe fused into the balanced
-// partial kernel run exactly this arithmetic, in this order, so their decisions are identical.
+// Routing signal (Section 4.2).  Four adjacent lanes share one query head: lane4 owns the 16-byte
+// chunks lane4, lane4+4, lane4+8, lane4+12 of the 256-byte row.  The standalone probe kernel and
+// the probe fused into the balanced partial kernel run exactly this arithmetic, in this order, so
+// their decisions are identical.
 // ------------------------------------------------------------------------------------------
 struct RouteRule {
   float tau[4], len_norm;
   int routing;
 };
 
-// Eq. 8 for one head; qw / kw are this lane's 8 elements of the query and of K_0.
-// anchor_norm < 0 means "recompute ||K_0||".  All 16 lanes of the head must be active.
-__device__ __forceinline__ float head_cosine(const uint4 qw, const uint4 kw, float anchor_norm) {
-  const uint32_t qs[4] = {qw.x, qw.y, qw.z, qw.w}, ks[4] = {kw.x, kw.y, kw.z, kw.w};
+// x + x of the lane whose index differs in bit 0 (kXor1) or bit 1 of the quad: one DPP move each.
+template <int kCtrl>
+__device__ __forceinline__ float quad_swap_add(float x) {
+  const int y = __builtin_amdgcn_update_dpp(0, __float_as_int(x), kCtrl, 0xF, 0xF, false);
+  return x + __int_as_float(y);
+}
+
+// Eq. 8 for one head; qw / kw are this lane's four chunks of the query and of K_0.
+// anchor_norm < 0 means "recompute ||K_0||".  All 4 lanes of the head must be active.
+__device__ __forceinline__ float head_cosine(const uint4 (&qw)[4], const uint4 (&kw)[4], float anchor_norm) {
   float dot = 0.f, qq = 0.f, kk = 0.f;
 #pragma unroll
-  for (int e = 0; e < 4; ++e) {
-    const float q0 = bf16_lo(qs[e]), q1 = bf16_hi(qs[e]), k0 = bf16_lo(ks[e]), k1 = bf16_hi(ks[e]);
-    dot = fmaf(q0, k0, dot); dot = fmaf(q1, k1, dot);
-    qq = fmaf(q0, q0, qq);   qq = fmaf(q1, q1, qq);
-    kk = fmaf(k0, k0, kk);   kk = fmaf(k1, k1, kk);
-  }
+  for (int j = 0; j < 4; ++j) {
+    const uint32_t qs[4] = {qw[j].x, qw[j].y, qw[j].z, qw[j].w}, ks[4] = {kw[j].x, kw[j].y, kw[j].z, kw[j].w};
 #pragma unroll
-  for (int o = 8; o >= 1; o >>= 1) {
-    dot += __shfl_xor(dot, o, 16);
-    qq += __shfl_xor(qq, o, 16);
-    kk += __shfl_xor(kk, o, 16);
+    for (int e = 0; e < 4; ++e) {
+      const float q0 = bf16_lo(qs[e]), q1 = bf16_hi(qs[e]), k0 = bf16_lo(ks[e]), k1 = bf16_hi(ks[e]);
+      dot = fmaf(q0, k0, dot); dot = fmaf(q1, k1, dot);
+      qq = fmaf(q0, q0, qq);   qq = fmaf(q1, q1, qq);
+      kk = fmaf(k0, k0, kk);   kk = fmaf(k1, k1, kk);
+    }
   }
+  dot = quad_swap_add<0xB1>(dot); qq = quad_swap_add<0xB1>(qq); kk = quad_swap_add<0xB1>(kk);   // quad_perm [1,0,3,2]
+  dot = quad_swap_add<0x4E>(dot); qq = quad_swap_add<0x4E>(qq); kk = quad_swap_add<0x4E>(kk);   // quad_perm [2,3,0,1]
   const float nk = anchor_norm >= 0.f ? anchor_norm : sqrtf(kk);
   const float den = sqrtf(qq) * nk;
   return (den > 0.f) ? dot / den : 0.f;
@@ -120,7 +135,7 @@ __device__ __forceinline__ bool route_decide(const float* cosines, int G, int L,
   return r.routing && L > 0 && S > tau;       // strict; NaN compares false, so the group stays active
 }
 
-// Standalone probe.  grid = B*H_kv, block = 256: 16 lanes per head, up to 16 heads.
+// Standalone probe.  grid = B*H_kv, block = 64: 4 lanes per head, up to 16 heads.
 struct ProbeArgs {
   const uint4* q;
   const uint4* k;
@@ -132,16 +147,19 @@ struct ProbeArgs {
   RouteRule rule;
 };
 
-__global__ __launch_bounds__(256) void sr_probe_kernel(ProbeArgs a) {
+__global__ __launch_bounds__(64) void sr_probe_kernel(ProbeArgs a) {
   __shared__ float cosv[kMaxGroup];
   const int bg = blockIdx.x;
   const int b = bg / a.Hkv, g = bg - b * a.Hkv;
-  const int lane16 = threadIdx.x & 15, i = threadIdx.x >> 4;
+  const int lane4 = threadIdx.x & 3, i = threadIdx.x >> 2;
   const int hd = i < a.G ? i : 0;
-  const uint4 kw = a.k[(size_t)bg * a.Lmax * (kD / 8) + lane16];          // row 0 of the group's keys
-  const uint4 qw = a.q[((size_t)b * a.Hq + (size_t)g * a.G + hd) * (kD / 8) + lane16];
+  const uint4* krow = a.k + (size_t)bg * a.Lmax * (kD / 8);                  // row 0 of the group's keys
+  const uint4* qrow = a.q + ((size_t)b * a.Hq + (size_t)g * a.G + hd) * (kD / 8);
+  uint4 qw[4], kw[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) { qw[j] = qrow[lane4 + 4 * j]; kw[j] = krow[lane4 + 4 * j]; }
   const float c = head_cosine(qw, kw, a.k0_norm ? a.k0_norm[bg] : -1.f);
-  if (lane16 == 0 && i < a.G) cosv[i] = c;
+  if (lane4 == 0 && i < a.G) cosv[i] = c;
   __syncthreads();
   if (threadIdx.x == 0) {
     float S;
@@ -170,6 +188,9 @@ struct PartialArgs {
   int chunk;        // fixed schedule: tokens per chunk
   int slots;        // partial records per head
   float scale_log2; // softmax scale * log2(e)
+#if SR_TIMELINE
+  long long* timeline;
+#endif
 };
 
 // K tile T, step j: lane (r16, kg) holds token tok0+16T+r16, elements (4j+kg)*8 .. +8.
@@ -364,8 +385,14 @@ __device__ __forceinline__ void attend_range(const PartialArgs& a, int b, int g,
 #pragma unroll
     for (int T = 0; T < 4; ++T) load_v_tile(vr[T], V4, tok0, T, r16, kg, last);
     int next = tok0 + kWaves * kBlock;
+#if SR_TIMELINE
+    bool first = true;
+#endif
     while (next < t_end) {
       block_step<true>(w, kr, vr, qb, K4, V4, tok0, next, t_end, last, r16, kg, a.scale_log2);
+#if SR_TIMELINE
+      if (first) { SR_STAMP(a, 2); first = false; }
+#endif
       tok0 = next;
       next += kWaves * kBlock;
     }
@@ -373,6 +400,7 @@ __device__ __forceinline__ void attend_range(const PartialArgs& a, int b, int g,
   }
 
   // ---- merge the 4 wavefronts through LDS, write one partial per head
+  SR_STAMP(a, 3);
   float l_run = w.l_run;
   l_run += __shfl_xor(l_run, 16, 64);
   l_run += __shfl_xor(l_run, 32, 64);
@@ -404,6 +432,7 @@ __device__ __forceinline__ void attend_range(const PartialArgs& a, int b, int g,
     *reinterpret_cast<float4*>(a.part_o + rec * kD + 4 * c4) = o;
     if (c4 == 0) *reinterpret_cast<float2*>(a.part_ml + rec * 2) = make_float2(M, l);
   }
+  SR_STAMP(a, 4);
 }
 
 // Fixed schedule.  grid = (num_splits, B*H_kv), block = 256.
@@ -436,29 +465,31 @@ __global__ __launch_bounds__(256, 2) void sr_partial_balanced_kernel(PartialArgs
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int NG = a.NG, G = a.G;
   const int p = blockIdx.x, P = gridDim.x;
+  SR_STAMP(a, 0);
   for (int i = tid; i < NG; i += 256) lens[i] = clamp_len(a.seq_lens[i / a.Hkv], a.Lmax);
-  if (kFused) {
-    const int NH = NG * G, lane16 = tid & 15;
+  if (kFused && a.rule.routing) {
+    const int NH = NG * G, lane4 = tid & 3;
     const uint4* q4 = reinterpret_cast<const uint4*>(a.q);
     const uint4* k4 = reinterpret_cast<const uint4*>(a.k);
-    constexpr int UN = 8;                        // 8 x 16 heads per sweep, all loads in flight at once
-    for (int h0 = 0; h0 < NH; h0 += 16 * UN) {
-      uint4 qw[UN], kw[UN];
-      float kn[UN];
+    for (int h0 = 0; h0 < NH; h0 += 128) {      // 64 heads per sweep, two sweeps in flight
+      uint4 qw[2][4], kw[2][4];
+      float kn[2];
 #pragma unroll
-      for (int u = 0; u < UN; ++u) {
-        int hd = h0 + 16 * u + (tid >> 4);
+      for (int u = 0; u < 2; ++u) {
+        int hd = h0 + 64 * u + (tid >> 2);
         hd = hd < NH ? hd : NH - 1;
         const int i = hd / G;
-        qw[u] = q4[(size_t)hd * (kD / 8) + lane16];
-        kw[u] = k4[(size_t)i * a.Lmax * (kD / 8) + lane16];
+        const uint4* qrow = q4 + (size_t)hd * (kD / 8);
+        const uint4* krow = k4 + (size_t)i * a.Lmax * (kD / 8);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { qw[u][j] = qrow[lane4 + 4 * j]; kw[u][j] = krow[lane4 + 4 * j]; }
         kn[u] = a.k0_norm ? a.k0_norm[i] : -1.f;
       }
 #pragma unroll
-      for (int u = 0; u < UN; ++u) {
-        const int hd = h0 + 16 * u + (tid >> 4);
+      for (int u = 0; u < 2; ++u) {
+        const int hd = h0 + 64 * u + (tid >> 2);
         const float cs = head_cosine(qw[u], kw[u], kn[u]);
-        if (lane16 == 0 && hd < NH) cosv[hd] = cs;
+        if (lane4 == 0 && hd < NH) cosv[hd] = cs;
       }
     }
   }
@@ -470,8 +501,8 @@ __global__ __launch_bounds__(256, 2) void sr_partial_balanced_kernel(PartialArgs
     if (i < NG) {
       bool skip;
       if (kFused) {
-        float S;
-        skip = route_decide(cosv + i * G, G, lens[i], a.rule, &S);
+        float S = 0.f;
+        skip = a.rule.routing ? route_decide(cosv + i * G, G, lens[i], a.rule, &S) : false;
         if (p == 0) { a.mask[i] = skip ? 1 : 0; if (a.group_score) a.group_score[i] = S; }
       } else {
         skip = a.mask[i] != 0;
@@ -503,6 +534,7 @@ __global__ __launch_bounds__(256, 2) void sr_partial_balanced_kernel(PartialArgs
     for (int i = tid; i <= NG; i += 256) a.sched[2 + i] = start[i];
   }
   const int u_lo = p * c, u_hi = min(u_lo + c, U);
+  SR_STAMP(a, 1);
   if (u_lo >= u_hi) return;
   for (int i = tid; i < NG; i += 256)
     if (start[i] <= u_lo && u_lo < start[i + 1]) first_group = i;   // exactly one group holds u_lo
@@ -516,6 +548,7 @@ __global__ __launch_bounds__(256, 2) void sr_partial_balanced_kernel(PartialArgs
     attend_range(a, b, g, L, blk_lo * kBlock, min(blk_hi * kBlock, L), p - s0 / c);
     __syncthreads();                            // LDS of attend_range is reused by the next segment
   }
+  SR_STAMP(a, 5);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -688,6 +721,9 @@ int make_layout(const sr_route_params* p, Layout* lay) {
   lay->off_score = lay->off_ml + align_up(heads * S * 2 * sizeof(float), 256);
   lay->off_sched = lay->off_score + align_up((size_t)NG * sizeof(float), 256);
   pl.workspace_bytes = lay->off_sched + align_up((size_t)(NG + 3) * sizeof(int32_t), 256);
+#if SR_TIMELINE
+  pl.workspace_bytes += (size_t)kBalancedGrid * 8 * sizeof(long long);   // last bytes of the workspace
+#endif
   return SR_OK;
 }
 
@@ -712,7 +748,7 @@ int launch_probe(const void* q, const void* k, const int32_t* seq_lens, const sr
   a.mask = mask;
   a.Hq = p->n_q_heads; a.Hkv = p->n_kv_heads; a.G = lay.plan.group_size; a.Lmax = p->max_seq_len;
   a.rule = make_rule(p);
-  hipLaunchKernelGGL(sr_probe_kernel, dim3(p->batch * p->n_kv_heads), dim3(256), 0, st, a);
+  hipLaunchKernelGGL(sr_probe_kernel, dim3(p->batch * p->n_kv_heads), dim3(64), 0, st, a);
   return hipGetLastError() == hipSuccess ? SR_OK : SR_ERR_HIP;
 }
 
@@ -754,6 +790,9 @@ int decode_impl(const void* q, const void* k, const void* v, const int32_t* seq_
     a.v = static_cast<const uint16_t*>(v);
     a.seq_lens = seq_lens; a.mask = mask; a.part_o = part_o; a.part_ml = part_ml; a.sched = sched;
     a.k0_norm = p->k0_norm; a.group_score = score; a.rule = make_rule(p);
+#if SR_TIMELINE
+    a.timeline = reinterpret_cast<long long*>(ws + lay.plan.workspace_bytes - (size_t)kBalancedGrid * 8 * sizeof(long long));
+#endif
     a.Hq = p->n_q_heads; a.Hkv = p->n_kv_heads; a.G = lay.plan.group_size; a.Lmax = p->max_seq_len;
     a.NG = p->batch * p->n_kv_heads;
     a.chunk = lay.plan.chunk_tokens; a.slots = lay.plan.slots_per_head;

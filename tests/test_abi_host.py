@@ -1,0 +1,165 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, its plan/workspace arithmetic is sane, and every argument error is reported
+before any HIP call.  (Compute calls are exercised by the -m gpu tests only.)"""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2604_16883_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "sinkrouter.h")
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sinkrouter_\w+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = B.load()
+    names = declared_functions()
+    assert len(names) >= 9
+    for n in names:
+        assert hasattr(lib, n), "libsinkrouter.so does not export %s" % n
+    assert B.sinkrouter_abi_version() == 1
+
+
+def test_binding_mirrors_header_structs():
+    text = open(HEADER).read()
+    body = re.search(r"typedef struct sr_route_params \{(.*?)\} sr_route_params;", text, re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    fields = re.findall(r"(\w+)(?:\[\d+\])?;", body)
+    assert fields == [f[0] for f in B.RouteParams._fields_]
+    body = re.search(r"typedef struct sr_plan \{(.*?)\} sr_plan;", text, re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    fields = re.findall(r"(\w+);", body)
+    assert fields == [f[0] for f in B.Plan._fields_]
+    # the library checks struct_size itself
+    p = B.make_route_params(1, 32, 8, 4096)
+    assert B.sinkrouter_workspace_bytes(p) > 0
+    p.struct_size += 8
+    assert B.sinkrouter_workspace_bytes(p) == 0
+
+
+def test_status_strings():
+    seen = set()
+    for code in (B.SR_OK, B.SR_ERR_NULL, B.SR_ERR_SHAPE, B.SR_ERR_UNSUPPORTED, B.SR_ERR_WORKSPACE, B.SR_ERR_ALIGN, B.SR_ERR_HIP):
+        s = B.sinkrouter_status_string(code)
+        assert s and s != "unknown status"
+        seen.add(s)
+    assert len(seen) == 7
+    assert B.sinkrouter_status_string(-99) == "unknown status"
+
+
+WORKLOAD_SHAPES = {"c0": (1, 32, 8, 4096), "c1": (4, 32, 8, 32768), "c2": (1, 32, 4, 200000),
+                   "c3": (1, 64, 8, 524288), "c4": (2, 40, 40, 65536)}
+
+
+@pytest.mark.parametrize("name", sorted(WORKLOAD_SHAPES))
+def test_plan_balanced(name):
+    b, hq, hkv, L = WORKLOAD_SHAPES[name]
+    pl = B.sinkrouter_plan(B.make_route_params(b, hq, hkv, L))
+    assert pl.schedule == 1 and pl.partial_grid == 512 and pl.group_size == hq // hkv
+    blocks = (L + 63) // 64
+    assert pl.slots_per_head == min(blocks, 513)
+    heads = b * hq
+    need = heads * pl.slots_per_head * (128 + 2) * 4
+    assert need <= pl.workspace_bytes <= need + 4096 + 8 * (b * hkv + 3) + 4 * b * hkv + 1024
+    assert B.sinkrouter_workspace_bytes(B.make_route_params(b, hq, hkv, L)) == pl.workspace_bytes
+
+
+@pytest.mark.parametrize("num_splits,L,chunk,splits", [(1, 4096, 4096, 1), (3, 4096, 1536, 3), (64, 4096, 256, 16),
+                                                       (7, 200000, 28672, 7), (200, 524288, 2816, 187)])
+def test_plan_fixed(num_splits, L, chunk, splits):
+    pl = B.sinkrouter_plan(B.make_route_params(2, 32, 8, L, num_splits=num_splits))
+    assert pl.schedule == 0
+    assert pl.chunk_tokens == chunk and pl.chunk_tokens % 256 == 0
+    assert pl.num_splits == splits == (L + chunk - 1) // chunk
+    assert pl.partial_grid == splits * 2 * 8 and pl.slots_per_head == splits
+
+
+def test_plan_falls_back_to_fixed_chunks_for_many_groups():
+    pl = B.sinkrouter_plan(B.make_route_params(512, 32, 8, 2048))      # 4096 (sequence, group) pairs
+    assert pl.schedule == 0 and pl.num_splits >= 1
+
+
+FAKE = dict(q=0x10000, k=0x20000, v=0x30000, sl=0x40000, out=0x50000, mask=0x60000, ws=0x70000)
+
+
+def call(p=None, **over):
+    a = dict(FAKE)
+    a.update(over)
+    if p is None:
+        p = B.make_route_params(1, 32, 8, 4096, workspace=a["ws"], workspace_bytes=1 << 30)
+    return B.sinkrouter_decode(a["q"], a["k"], a["v"], a["sl"], p, a["out"], a["mask"], check=False)
+
+
+def test_null_pointers_are_rejected():
+    for key in ("q", "k", "v", "sl", "out", "mask"):
+        assert call(**{key: None}) == B.SR_ERR_NULL, key
+    lib = B.load()
+    assert lib.sinkrouter_decode(1 << 16, 1 << 17, 1 << 18, 1 << 19, None, 1 << 20, 1 << 21) == B.SR_ERR_NULL
+    assert lib.sinkrouter_plan(None, None) == B.SR_ERR_NULL
+    p = B.make_route_params(1, 32, 8, 4096, workspace=FAKE["ws"], workspace_bytes=1 << 30)
+    assert lib.sinkrouter_decode_profiled(1 << 16, 1 << 17, 1 << 18, 1 << 19, ctypes.byref(p), 1 << 20, 1 << 21, None) == B.SR_ERR_NULL
+    assert B.sinkrouter_probe(None, FAKE["k"], FAKE["sl"], p, None, FAKE["mask"], check=False) == B.SR_ERR_NULL
+    assert B.sinkrouter_probe(FAKE["q"], FAKE["k"], FAKE["sl"], p, None, None, check=False) == B.SR_ERR_NULL
+    assert lib.sinkrouter_hbm_read_probe(None, 1024, 1 << 16, None) == B.SR_ERR_NULL
+    assert lib.sinkrouter_hbm_copy_probe(1 << 16, None, 1024, None) == B.SR_ERR_NULL
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(batch=0), B.SR_ERR_SHAPE), (dict(n_q_heads=0), B.SR_ERR_SHAPE), (dict(n_kv_heads=0), B.SR_ERR_SHAPE),
+    (dict(max_seq_len=0), B.SR_ERR_SHAPE), (dict(n_q_heads=33), B.SR_ERR_SHAPE), (dict(num_splits=-1), B.SR_ERR_SHAPE),
+    (dict(max_seq_len=(1 << 24) + 1), B.SR_ERR_SHAPE), (dict(batch=70000, n_kv_heads=1, n_q_heads=1), B.SR_ERR_SHAPE),
+    (dict(sm_scale=-1.0), B.SR_ERR_SHAPE), (dict(sm_scale=float("nan")), B.SR_ERR_SHAPE),
+    (dict(head_dim=64), B.SR_ERR_UNSUPPORTED), (dict(kv_block=128), B.SR_ERR_UNSUPPORTED),
+    (dict(n_q_heads=136, n_kv_heads=8), B.SR_ERR_UNSUPPORTED),
+])
+def test_bad_shapes(kw, code):
+    base = dict(batch=1, n_q_heads=32, n_kv_heads=8, max_seq_len=4096, head_dim=128, kv_block=64, num_splits=0, sm_scale=0.0)
+    base.update(kw)
+    p = B.make_route_params(base["batch"], base["n_q_heads"], base["n_kv_heads"], base["max_seq_len"],
+                            head_dim=base["head_dim"], kv_block=base["kv_block"], num_splits=base["num_splits"],
+                            sm_scale=base["sm_scale"], workspace=FAKE["ws"], workspace_bytes=1 << 40)
+    assert call(p) == code
+    assert B.sinkrouter_workspace_bytes(p) == 0
+    with pytest.raises(B.SinkRouterError) as e:
+        B.sinkrouter_plan(p)
+    assert e.value.status == code
+
+
+def test_alignment_and_workspace_errors():
+    for key in ("q", "k", "v", "out"):
+        assert call(**{key: FAKE[key] + 8}) == B.SR_ERR_ALIGN, key
+    assert call(sl=FAKE["sl"] + 2) == B.SR_ERR_ALIGN
+    need = B.sinkrouter_workspace_bytes(B.make_route_params(1, 32, 8, 4096))
+    assert call(B.make_route_params(1, 32, 8, 4096)) == B.SR_ERR_WORKSPACE                       # no workspace
+    assert call(B.make_route_params(1, 32, 8, 4096, workspace=FAKE["ws"], workspace_bytes=need - 1)) == B.SR_ERR_WORKSPACE
+    assert call(B.make_route_params(1, 32, 8, 4096, workspace=FAKE["ws"] + 128, workspace_bytes=need)) == B.SR_ERR_WORKSPACE
+    lib = B.load()
+    assert lib.sinkrouter_hbm_read_probe(1 << 16, 1000, 1 << 17, None) == B.SR_ERR_SHAPE
+    assert lib.sinkrouter_hbm_read_probe((1 << 16) + 4, 1024, 1 << 17, None) == B.SR_ERR_ALIGN
+
+
+def test_compute_call_without_gpu_fails_loudly():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    # valid arguments, no device: the HIP launch fails and the library says so; nothing falls back to the CPU
+    assert call() == B.SR_ERR_HIP
+    with pytest.raises(B.SinkRouterError):
+        B.sinkrouter_decode(FAKE["q"], FAKE["k"], FAKE["v"], FAKE["sl"],
+                            B.make_route_params(1, 32, 8, 4096, workspace=FAKE["ws"], workspace_bytes=1 << 30),
+                            FAKE["out"], FAKE["mask"])
+
+
+def test_missing_library_raises(tmp_path, monkeypatch):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(FileNotFoundError):
+        B.load()
