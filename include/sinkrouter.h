@@ -93,8 +93,8 @@ typedef struct sr_plan {
  *                           to 256 tokens), one workgroup per (chunk, sequence, KV group), as
  *                           the paper states it; workgroups of Sink Groups exit immediately.
  *   params->num_splits == 0 "balanced": the 64-token blocks of the Active Groups only are dealt
- *                           out in equal contiguous shares to a grid that just fills the chip
- *                           (512 workgroups), so the chunk length adapts to the skip pattern.
+ *                           out in equal contiguous shares to one workgroup per compute unit
+ *                           (256), so the chunk length adapts to the skip pattern.
  *                           Needs B*H_kv <= 2048; larger batches fall back to fixed chunks.
  * The result does not depend on the schedule beyond fp32 rounding.
  */

@@ -13,7 +13,7 @@
 //                      softmax per block.  The 4 wavefronts of a workgroup interleave blocks
 //                      and merge their results through LDS into one partial (m, l, o) per
 //                      (head, workgroup).  Two schedules:
-//        balanced  (default) a grid that just fills the chip; every workgroup first scans the
+//        balanced  (default) one workgroup per compute unit; every workgroup first scans the
 //                  skip mask, so the 64-token blocks of the Active Groups only are dealt out
 //                  in equal contiguous shares.  Sink Groups cost nothing and the chip stays
 //                  full whatever the skip pattern is.
@@ -52,12 +52,19 @@ namespace {
 
 constexpr int kD = 128;              // head dimension
 constexpr int kBlock = 64;           // tokens per online-softmax block (B_K)
-constexpr int kWaves = 4;            // wavefronts per partial workgroup
+#ifndef SR_WAVES
+#define SR_WAVES 4
+#endif
+constexpr int kWaves = SR_WAVES;     // wavefronts per partial workgroup
+constexpr int kThreads = 64 * kWaves;
 constexpr int kMaxGroup = 16;        // query heads per KV group that fit the MFMA tile
 constexpr int kChunkUnit = kBlock * kWaves;
 constexpr int kOStride = kD + 4;     // LDS row stride (floats) of the per-wave output tile
 constexpr int kCombineThreads = 1024;
-constexpr int kBalancedGrid = 512;   // 256 compute units x 2 resident workgroups (228 VGPRs each)
+#ifndef SR_GRID
+#define SR_GRID 256
+#endif
+constexpr int kBalancedGrid = SR_GRID;   // one workgroup per compute unit: measured best (512 and 1024 are 3-6% slower)
 constexpr int kMaxSchedGroups = 2048;  // (sequence, KV group) pairs the balanced schedule scans in LDS
 constexpr int kMaxFusedHeads = 512;    // query heads (all sequences) the balanced kernel probes itself
 
@@ -415,7 +422,7 @@ __device__ __forceinline__ void attend_range(const PartialArgs& a, int b, int g,
   }
   __syncthreads();
   const int c4 = threadIdx.x & 31;            // float4 column
-  for (int h = threadIdx.x >> 5; h < G; h += 8) {
+  for (int h = threadIdx.x >> 5; h < G; h += kThreads / 32) {
     float M = lds_m[0][h];
 #pragma unroll
     for (int u = 1; u < kWaves; ++u) M = fmaxf(M, lds_m[u][h]);
@@ -436,7 +443,7 @@ __device__ __forceinline__ void attend_range(const PartialArgs& a, int b, int g,
 }
 
 // Fixed schedule.  grid = (num_splits, B*H_kv), block = 256.
-__global__ __launch_bounds__(256, 2) void sr_partial_fixed_kernel(PartialArgs a) {
+__global__ __launch_bounds__(kThreads, 2) void sr_partial_fixed_kernel(PartialArgs a) {
   const int s = blockIdx.x;
   const int bg = blockIdx.y;
   if (a.mask[bg]) return;                       // Sink Group: no K/V row is touched
@@ -456,7 +463,7 @@ __global__ __launch_bounds__(256, 2) void sr_partial_fixed_kernel(PartialArgs a)
 // separate probe launch precedes it; workgroup 0 writes skip mask and group scores.  Otherwise
 // the mask written by sr_probe_kernel is read.
 template <bool kFused>
-__global__ __launch_bounds__(256, 2) void sr_partial_balanced_kernel(PartialArgs a) {
+__global__ __launch_bounds__(kThreads, 2) void sr_partial_balanced_kernel(PartialArgs a) {
   __shared__ int start[kMaxSchedGroups + 1];
   __shared__ int lens[kMaxSchedGroups];
   __shared__ float cosv[kFused ? kMaxFusedHeads : 1];
@@ -466,17 +473,17 @@ __global__ __launch_bounds__(256, 2) void sr_partial_balanced_kernel(PartialArgs
   const int NG = a.NG, G = a.G;
   const int p = blockIdx.x, P = gridDim.x;
   SR_STAMP(a, 0);
-  for (int i = tid; i < NG; i += 256) lens[i] = clamp_len(a.seq_lens[i / a.Hkv], a.Lmax);
+  for (int i = tid; i < NG; i += kThreads) lens[i] = clamp_len(a.seq_lens[i / a.Hkv], a.Lmax);
   if (kFused && a.rule.routing) {
     const int NH = NG * G, lane4 = tid & 3;
     const uint4* q4 = reinterpret_cast<const uint4*>(a.q);
     const uint4* k4 = reinterpret_cast<const uint4*>(a.k);
-    for (int h0 = 0; h0 < NH; h0 += 128) {      // 64 heads per sweep, two sweeps in flight
+    for (int h0 = 0; h0 < NH; h0 += kThreads / 2) {      // kThreads/4 heads per sweep, two sweeps in flight
       uint4 qw[2][4], kw[2][4];
       float kn[2];
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
-        int hd = h0 + 64 * u + (tid >> 2);
+        int hd = h0 + (kThreads / 4) * u + (tid >> 2);
         hd = hd < NH ? hd : NH - 1;
         const int i = hd / G;
         const uint4* qrow = q4 + (size_t)hd * (kD / 8);
@@ -487,7 +494,7 @@ __global__ __launch_bounds__(256, 2) void sr_partial_balanced_kernel(PartialArgs
       }
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
-        const int hd = h0 + 64 * u + (tid >> 2);
+        const int hd = h0 + (kThreads / 4) * u + (tid >> 2);
         const float cs = head_cosine(qw[u], kw[u], kn[u]);
         if (lane4 == 0 && hd < NH) cosv[hd] = cs;
       }
@@ -495,7 +502,7 @@ __global__ __launch_bounds__(256, 2) void sr_partial_balanced_kernel(PartialArgs
   }
   __syncthreads();
   int carry = 0;
-  for (int base = 0; base < NG; base += 256) {
+  for (int base = 0; base < NG; base += kThreads) {
     const int i = base + tid;
     int u = 0;
     if (i < NG) {
@@ -520,7 +527,9 @@ __global__ __launch_bounds__(256, 2) void sr_partial_balanced_kernel(PartialArgs
     int woff = 0;
 #pragma unroll
     for (int u2 = 0; u2 < kWaves; ++u2) if (u2 < wave) woff += wsum[u2];
-    const int tot = wsum[0] + wsum[1] + wsum[2] + wsum[3];
+    int tot = 0;
+#pragma unroll
+    for (int u2 = 0; u2 < kWaves; ++u2) tot += wsum[u2];
     if (i < NG) start[i] = carry + woff + x - u;
     carry += tot;
     __syncthreads();
@@ -531,12 +540,12 @@ __global__ __launch_bounds__(256, 2) void sr_partial_balanced_kernel(PartialArgs
   __syncthreads();
   if (p == 0) {
     if (tid == 0) { a.sched[0] = U; a.sched[1] = c; }
-    for (int i = tid; i <= NG; i += 256) a.sched[2 + i] = start[i];
+    for (int i = tid; i <= NG; i += kThreads) a.sched[2 + i] = start[i];
   }
   const int u_lo = p * c, u_hi = min(u_lo + c, U);
   SR_STAMP(a, 1);
   if (u_lo >= u_hi) return;
-  for (int i = tid; i < NG; i += 256)
+  for (int i = tid; i < NG; i += kThreads)
     if (start[i] <= u_lo && u_lo < start[i + 1]) first_group = i;   // exactly one group holds u_lo
   __syncthreads();
   for (int i = first_group; i < NG && start[i] < u_hi; ++i) {

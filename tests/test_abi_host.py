@@ -63,9 +63,9 @@ WORKLOAD_SHAPES = {"c0": (1, 32, 8, 4096), "c1": (4, 32, 8, 32768), "c2": (1, 32
 def test_plan_balanced(name):
     b, hq, hkv, L = WORKLOAD_SHAPES[name]
     pl = B.sinkrouter_plan(B.make_route_params(b, hq, hkv, L))
-    assert pl.schedule == 1 and pl.partial_grid == 512 and pl.group_size == hq // hkv
+    assert pl.schedule == 1 and pl.partial_grid == 256 and pl.group_size == hq // hkv
     blocks = (L + 63) // 64
-    assert pl.slots_per_head == min(blocks, 513)
+    assert pl.slots_per_head == min(blocks, 257)
     heads = b * hq
     need = heads * pl.slots_per_head * (128 + 2) * 4
     assert need <= pl.workspace_bytes <= need + 4096 + 8 * (b * hkv + 3) + 4 * b * hkv + 1024
