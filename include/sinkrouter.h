@@ -68,7 +68,9 @@ typedef struct sr_route_params {
   float tau_coef[4];        /* a, b, c, d */
   float len_norm;           /* x = seq_len / len_norm; <= 0 means x = 0 */
   const float* k0_norm;     /* device, optional [B,H_kv]: ||K_0||_2 cached at prefill
-                               (Section 4.1); NULL = recompute from row 0 */
+                               (Section 4.1, Eq. 7); NULL = recompute from the anchor */
+  const void* k0;           /* device, optional bf16 [B,H_kv,D]: the token-0 keys kept apart from
+                               the cache (the K_0 tensor of Section 4.3); NULL = row 0 of k_cache */
   void* workspace;          /* device, 256-byte aligned, >= sinkrouter_workspace_bytes() */
   size_t workspace_bytes;
   void* stream;             /* hipStream_t; NULL = the default stream */
@@ -144,6 +146,30 @@ int sinkrouter_decode_profiled(const void* q, const void* k_cache, const void* v
                                void* out, uint8_t* skip_mask_out, float* stage_us);
 
 /*
+ * sinkrouter_decode with two per-head diagnostics of the attention it computed (at least one of
+ * the two pointers non-NULL):
+ *   lse_out    device fp32 [B,H_q]: natural-log sum-exp of the scaled scores
+ *   alpha0_out device fp32 [B,H_q]: softmax mass on token 0, the quantity whose exceeding gamma
+ *              defines the target regime the routing signal stands in for (Section 4.2, first
+ *              paragraph; Appendix C measures the proxy against it)
+ * Heads of Sink Groups are not computed: both are NaN there (run with routing_enabled = 0 to get
+ * them for every head).  An empty sequence gives lse = -inf, alpha0 = NaN.
+ */
+int sinkrouter_decode_diag(const void* q, const void* k_cache, const void* v_cache,
+                           const int32_t* seq_lens, const sr_route_params* params,
+                           void* out, uint8_t* skip_mask_out, float* lse_out, float* alpha0_out);
+
+/*
+ * Prefill-side anchor caching (Section 4.1): copies row 0 of every (sequence, KV group) key cache
+ * to k0_out (device bf16 [B,H_kv,D], optional) and writes its Euclidean norm to k0_norm_out
+ * (device fp32 [B,H_kv], optional); at least one must be given.  The norm is computed exactly as
+ * the probe recomputes it, so passing these back through params->k0 / params->k0_norm leaves
+ * every routing decision unchanged.  Uses params for the shape and the stream only.
+ */
+int sinkrouter_extract_anchor(const void* k_cache, const sr_route_params* params,
+                              void* k0_out, float* k0_norm_out);
+
+/*
  * Measurement helpers (no part of the method): a streaming read of `bytes` bytes of device
  * memory (128-bit loads, every byte read once, one 4-byte result per workgroup written to
  * sink, which must hold at least 4096 bytes), and a plain device-to-device copy kernel of
@@ -158,7 +184,7 @@ const char* sinkrouter_status_string(int status);
 
 /* ABI version of this header: bumped on any incompatible change. */
 int sinkrouter_abi_version(void);
-#define SINKROUTER_ABI_VERSION 1
+#define SINKROUTER_ABI_VERSION 2
 
 #ifdef __cplusplus
 }

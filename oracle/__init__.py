@@ -110,13 +110,25 @@ def _cfg(B, Hq, Hkv, D, Lmax, routing_enabled, want_dense, sm_scale, tau_coef, l
     return c
 
 
+_keep = []
+
+
+def _anchors(k0, B, Hkv, D):
+    """Optional separately cached token-0 keys [B,Hkv,D] (uint16 bf16 bits) as a C pointer."""
+    if k0 is None:
+        return None
+    a = _u16(k0, (B, Hkv, D))
+    _keep[:] = [a]          # keep the contiguous copy alive during the call
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_uint16))
+
+
 def _ptr(a, ty):
     return a.ctypes.data_as(ctypes.POINTER(ty)) if a is not None else None
 
 
 def decode(q, k_cache, v_cache, seq_lens, *, tau_coef: Sequence[float] = (0.0, 0.0, 0.0, 0.55),
            len_norm: float = 0.0, sm_scale: float = 0.0, routing_enabled: bool = True,
-           k0_norm=None, want_dense: bool = False, diagnostics: bool = True,
+           k0_norm=None, k0=None, want_dense: bool = False, diagnostics: bool = True,
            libpath: Optional[str] = None) -> OracleResult:
     """Routed decode attention in fp64 (single pass over each head's scores).
 
@@ -149,7 +161,7 @@ def decode(q, k_cache, v_cache, seq_lens, *, tau_coef: Sequence[float] = (0.0, 0
     dp = ctypes.c_double
     rc = lib.sr_oracle_decode(
         _ptr(q, ctypes.c_uint16), _ptr(k_cache, ctypes.c_uint16), _ptr(v_cache, ctypes.c_uint16),
-        _ptr(sl, ctypes.c_int32), _ptr(kn, dp), ctypes.byref(c),
+        _ptr(sl, ctypes.c_int32), _ptr(kn, dp), _anchors(k0, B, Hkv, D), ctypes.byref(c),
         _ptr(out, dp), _ptr(mask, ctypes.c_uint8), _ptr(head_cos, dp), _ptr(group_score, dp),
         _ptr(tau, dp), _ptr(dense, dp), _ptr(alpha0, dp), _ptr(lse, dp))
     if rc != 0:
@@ -158,7 +170,7 @@ def decode(q, k_cache, v_cache, seq_lens, *, tau_coef: Sequence[float] = (0.0, 0
 
 
 def route(q, k_cache, seq_lens, *, tau_coef=(0.0, 0.0, 0.0, 0.55), len_norm: float = 0.0,
-          routing_enabled: bool = True, k0_norm=None, libpath: Optional[str] = None) -> OracleResult:
+          routing_enabled: bool = True, k0_norm=None, k0=None, libpath: Optional[str] = None) -> OracleResult:
     """Routing decision only (cosine, group mean, threshold); reads row 0 of k_cache."""
     lib = _load(libpath)
     q = np.ascontiguousarray(q)
@@ -179,7 +191,7 @@ def route(q, k_cache, seq_lens, *, tau_coef=(0.0, 0.0, 0.0, 0.55), len_norm: flo
     dp = ctypes.c_double
     rc = lib.sr_oracle_route(
         _ptr(q, ctypes.c_uint16), _ptr(k_cache, ctypes.c_uint16), _ptr(sl, ctypes.c_int32),
-        _ptr(kn, dp), ctypes.byref(c), _ptr(head_cos, dp), _ptr(group_score, dp),
+        _ptr(kn, dp), _anchors(k0, B, Hkv, D), ctypes.byref(c), _ptr(head_cos, dp), _ptr(group_score, dp),
         _ptr(tau, dp), _ptr(mask, ctypes.c_uint8))
     if rc != 0:
         raise RuntimeError("sr_oracle_route failed: %d" % rc)
@@ -188,7 +200,7 @@ def route(q, k_cache, seq_lens, *, tau_coef=(0.0, 0.0, 0.0, 0.55), len_norm: flo
 
 def decode_splitk(q, k_cache, v_cache, seq_lens, bounds, *, tau_coef=(0.0, 0.0, 0.0, 0.55),
                   len_norm: float = 0.0, sm_scale: float = 0.0, routing_enabled: bool = True,
-                  k0_norm=None, libpath: Optional[str] = None):
+                  k0_norm=None, k0=None, libpath: Optional[str] = None):
     """Routed decode attention reached through Split-K partials and the log-sum-exp merge.
 
     bounds: non-decreasing ints, bounds[0] == 0, bounds[-1] >= max(seq_lens).
@@ -216,7 +228,7 @@ def decode_splitk(q, k_cache, v_cache, seq_lens, bounds, *, tau_coef=(0.0, 0.0, 
     dp = ctypes.c_double
     rc = lib.sr_oracle_decode_splitk(
         _ptr(q, ctypes.c_uint16), _ptr(k_cache, ctypes.c_uint16), _ptr(v_cache, ctypes.c_uint16),
-        _ptr(sl, ctypes.c_int32), _ptr(kn, dp), ctypes.byref(c), _ptr(bnd, ctypes.c_int32),
+        _ptr(sl, ctypes.c_int32), _ptr(kn, dp), _anchors(k0, B, Hkv, D), ctypes.byref(c), _ptr(bnd, ctypes.c_int32),
         ctypes.c_int32(S), _ptr(out, dp), _ptr(mask, ctypes.c_uint8), _ptr(pm, dp), _ptr(pl, dp))
     if rc != 0:
         raise RuntimeError("sr_oracle_decode_splitk failed: %d" % rc)

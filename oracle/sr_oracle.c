@@ -130,14 +130,15 @@ static void head_partial(const uint16_t* q, const uint16_t* K, const uint16_t* V
 }
 
 /*
- * Routing only (Eq. 8-10).  All outputs optional except mask.
+ * Routing only (Eq. 8-10).  All outputs optional except mask.  k0_rows (optional) overrides
+ * the anchors read from row 0 of k_cache.
  *   head_cos    [B,H_q]   s_{g,i}
  *   group_score [B,H_kv]  S_g
  *   tau_out     [B]
  *   mask        [B,H_kv]  1 = Sink Group
  */
 int sr_oracle_route(const uint16_t* q, const uint16_t* k_cache, const int32_t* seq_lens,
-                    const double* k0_norm, const sr_oracle_cfg* c,
+                    const double* k0_norm, const uint16_t* k0_rows, const sr_oracle_cfg* c,
                     double* head_cos, double* group_score, double* tau_out, uint8_t* mask) {
   if (!q || !k_cache || !seq_lens || !c || !mask) return -1;
   const int B = c->batch, Hq = c->n_q_heads, Hkv = c->n_kv_heads, D = c->head_dim;
@@ -148,7 +149,9 @@ int sr_oracle_route(const uint16_t* q, const uint16_t* k_cache, const int32_t* s
     double tau = tau_of(c, L);
     if (tau_out) tau_out[b] = tau;
     for (int g = 0; g < Hkv; ++g) {
-      const uint16_t* k0 = k_cache + ((size_t)b * Hkv + g) * (size_t)c->max_seq_len * D;
+      /* the anchor: row 0 of the group's key cache, or the separately cached K_0 [B,H_kv,D] (Section 4.3) */
+      const uint16_t* k0 = k0_rows ? k0_rows + ((size_t)b * Hkv + g) * D
+                                   : k_cache + ((size_t)b * Hkv + g) * (size_t)c->max_seq_len * D;
       double an = k0_norm ? k0_norm[b * Hkv + g] : -1.0;
       double S = 0.0;
       for (int i = 0; i < r; ++i) {
@@ -175,11 +178,12 @@ int sr_oracle_route(const uint16_t* q, const uint16_t* k_cache, const int32_t* s
  * (else NaN).  Returns 0, or a negative value for bad arguments.
  */
 int sr_oracle_decode(const uint16_t* q, const uint16_t* k_cache, const uint16_t* v_cache,
-                     const int32_t* seq_lens, const double* k0_norm, const sr_oracle_cfg* c,
+                     const int32_t* seq_lens, const double* k0_norm, const uint16_t* k0_rows,
+                     const sr_oracle_cfg* c,
                      double* out, uint8_t* mask, double* head_cos, double* group_score,
                      double* tau_out, double* dense_out, double* alpha0, double* lse) {
   if (!v_cache || !out) return -1;
-  int rc = sr_oracle_route(q, k_cache, seq_lens, k0_norm, c, head_cos, group_score, tau_out, mask);
+  int rc = sr_oracle_route(q, k_cache, seq_lens, k0_norm, k0_rows, c, head_cos, group_score, tau_out, mask);
   if (rc) return rc;
   const int B = c->batch, Hq = c->n_q_heads, Hkv = c->n_kv_heads, D = c->head_dim;
   const int r = Hq / Hkv;
@@ -238,11 +242,11 @@ int sr_oracle_decode(const uint16_t* q, const uint16_t* k_cache, const uint16_t*
  * Optional outputs part_m / part_l [B,H_q,n_splits] expose the partial stats.
  */
 int sr_oracle_decode_splitk(const uint16_t* q, const uint16_t* k_cache, const uint16_t* v_cache,
-                            const int32_t* seq_lens, const double* k0_norm,
+                            const int32_t* seq_lens, const double* k0_norm, const uint16_t* k0_rows,
                             const sr_oracle_cfg* c, const int32_t* bounds, int32_t n_splits,
                             double* out, uint8_t* mask, double* part_m, double* part_l) {
   if (!v_cache || !out || !bounds || n_splits < 1) return -1;
-  int rc = sr_oracle_route(q, k_cache, seq_lens, k0_norm, c, NULL, NULL, NULL, mask);
+  int rc = sr_oracle_route(q, k_cache, seq_lens, k0_norm, k0_rows, c, NULL, NULL, NULL, mask);
   if (rc) return rc;
   for (int j = 0; j < n_splits; ++j)
     if (bounds[j] > bounds[j + 1]) return -2;

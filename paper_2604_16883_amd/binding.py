@@ -41,6 +41,7 @@ class RouteParams(ctypes.Structure):
         ("tau_coef", ctypes.c_float * 4),
         ("len_norm", ctypes.c_float),
         ("k0_norm", ctypes.c_void_p),
+        ("k0", ctypes.c_void_p),
         ("workspace", ctypes.c_void_p),
         ("workspace_bytes", ctypes.c_size_t),
         ("stream", ctypes.c_void_p),
@@ -88,6 +89,10 @@ def load() -> ctypes.CDLL:
         lib.sinkrouter_decode.restype = ctypes.c_int
         lib.sinkrouter_decode_profiled.argtypes = [vp, vp, vp, i32p, pp, vp, vp, ctypes.POINTER(ctypes.c_float)]
         lib.sinkrouter_decode_profiled.restype = ctypes.c_int
+        lib.sinkrouter_decode_diag.argtypes = [vp, vp, vp, i32p, pp, vp, vp, vp, vp]
+        lib.sinkrouter_decode_diag.restype = ctypes.c_int
+        lib.sinkrouter_extract_anchor.argtypes = [vp, pp, vp, vp]
+        lib.sinkrouter_extract_anchor.restype = ctypes.c_int
         lib.sinkrouter_probe.argtypes = [vp, vp, i32p, pp, vp, vp]
         lib.sinkrouter_probe.restype = ctypes.c_int
         lib.sinkrouter_hbm_read_probe.argtypes = [vp, ctypes.c_size_t, vp, vp]
@@ -123,7 +128,7 @@ def make_route_params(batch: int, n_q_heads: int, n_kv_heads: int, max_seq_len: 
                       head_dim: int = 128, kv_block: int = 64, num_splits: int = 0,
                       routing_enabled: bool = True, sm_scale: float = 0.0,
                       tau_coef: Sequence[float] = (0.0, 0.0, 0.0, 0.55), len_norm: float = 0.0,
-                      k0_norm=None, workspace=None, workspace_bytes: Optional[int] = None,
+                      k0_norm=None, k0=None, workspace=None, workspace_bytes: Optional[int] = None,
                       stream: Optional[int] = None) -> RouteParams:
     """Fill an ``sr_route_params``.  ``workspace`` is a device tensor (kept alive by the caller)."""
     p = RouteParams()
@@ -137,6 +142,7 @@ def make_route_params(batch: int, n_q_heads: int, n_kv_heads: int, max_seq_len: 
         p.tau_coef[i] = float(tau_coef[i])
     p.len_norm = float(len_norm)
     p.k0_norm = _addr(k0_norm)
+    p.k0 = _addr(k0)
     p.workspace = _addr(workspace)
     if workspace_bytes is None and workspace is not None and not isinstance(workspace, int):
         workspace_bytes = workspace.numel() * workspace.element_size()
@@ -194,6 +200,26 @@ def sinkrouter_decode_profiled(q, k_cache, v_cache, seq_lens, route_params: Rout
     if rc != SR_OK:
         raise SinkRouterError(rc, "sinkrouter_decode_profiled")
     return tuple(float(x) for x in us)
+
+
+def sinkrouter_decode_diag(q, k_cache, v_cache, seq_lens, route_params: RouteParams, out, skip_mask_out,
+                           lse_out, alpha0_out, check: bool = True) -> int:
+    """sinkrouter_decode plus per-head log-sum-exp and token-0 softmax mass (either may be None)."""
+    p = _with_stream(route_params)
+    rc = load().sinkrouter_decode_diag(_addr(q), _addr(k_cache), _addr(v_cache), _addr(seq_lens), ctypes.byref(p),
+                                       _addr(out), _addr(skip_mask_out), _addr(lse_out), _addr(alpha0_out))
+    if check and rc != SR_OK:
+        raise SinkRouterError(rc, "sinkrouter_decode_diag")
+    return rc
+
+
+def sinkrouter_extract_anchor(k_cache, route_params: RouteParams, k0_out, k0_norm_out, check: bool = True) -> int:
+    """Copy the token-0 keys and their norms out of the cache (prefill-side anchor caching)."""
+    p = _with_stream(route_params)
+    rc = load().sinkrouter_extract_anchor(_addr(k_cache), ctypes.byref(p), _addr(k0_out), _addr(k0_norm_out))
+    if check and rc != SR_OK:
+        raise SinkRouterError(rc, "sinkrouter_extract_anchor")
+    return rc
 
 
 def sinkrouter_probe(q, k_cache, seq_lens, route_params: RouteParams, group_score_out, skip_mask_out,

@@ -91,6 +91,13 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
 
 __device__ __forceinline__ int clamp_len(int L, int Lmax) { return L < 0 ? 0 : (L > Lmax ? Lmax : L); }
 
+// K_0 of (sequence, KV group) bg: row bg of the separately cached anchors [B,H_kv,D] when the caller
+// keeps them (Section 4.3 layout), else row 0 of the group's key cache.
+__device__ __forceinline__ const uint4* anchor_row(const void* k_cache, const void* k0, int bg, int Lmax) {
+  return k0 ? static_cast<const uint4*>(k0) + (size_t)bg * (kD / 8)
+            : static_cast<const uint4*>(k_cache) + (size_t)bg * Lmax * (kD / 8);
+}
+
 // ------------------------------------------------------------------------------------------
 // Routing signal (Section 4.2).  Four adjacent lanes share one query head: lane4 owns the 16-byte
 // chunks lane4, lane4+4, lane4+8, lane4+12 of the 256-byte row.  The standalone probe kernel and
@@ -109,10 +116,27 @@ __device__ __forceinline__ float quad_swap_add(float x) {
   return x + __int_as_float(y);
 }
 
+// Sum of squares of one 256-byte row held by a quad (4 chunks per lane): ||K_0||^2 of Eq. 7.
+__device__ __forceinline__ float quad_sumsq(const uint4 (&kw)[4]) {
+  float kk = 0.f;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const uint32_t ks[4] = {kw[j].x, kw[j].y, kw[j].z, kw[j].w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float k0 = bf16_lo(ks[e]), k1 = bf16_hi(ks[e]);
+      kk = fmaf(k0, k0, kk);
+      kk = fmaf(k1, k1, kk);
+    }
+  }
+  kk = quad_swap_add<0xB1>(kk);
+  return quad_swap_add<0x4E>(kk);
+}
+
 // Eq. 8 for one head; qw / kw are this lane's four chunks of the query and of K_0.
 // anchor_norm < 0 means "recompute ||K_0||".  All 4 lanes of the head must be active.
 __device__ __forceinline__ float head_cosine(const uint4 (&qw)[4], const uint4 (&kw)[4], float anchor_norm) {
-  float dot = 0.f, qq = 0.f, kk = 0.f;
+  float dot = 0.f, qq = 0.f;
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const uint32_t qs[4] = {qw[j].x, qw[j].y, qw[j].z, qw[j].w}, ks[4] = {kw[j].x, kw[j].y, kw[j].z, kw[j].w};
@@ -121,12 +145,11 @@ __device__ __forceinline__ float head_cosine(const uint4 (&qw)[4], const uint4 (
       const float q0 = bf16_lo(qs[e]), q1 = bf16_hi(qs[e]), k0 = bf16_lo(ks[e]), k1 = bf16_hi(ks[e]);
       dot = fmaf(q0, k0, dot); dot = fmaf(q1, k1, dot);
       qq = fmaf(q0, q0, qq);   qq = fmaf(q1, q1, qq);
-      kk = fmaf(k0, k0, kk);   kk = fmaf(k1, k1, kk);
     }
   }
-  dot = quad_swap_add<0xB1>(dot); qq = quad_swap_add<0xB1>(qq); kk = quad_swap_add<0xB1>(kk);   // quad_perm [1,0,3,2]
-  dot = quad_swap_add<0x4E>(dot); qq = quad_swap_add<0x4E>(qq); kk = quad_swap_add<0x4E>(kk);   // quad_perm [2,3,0,1]
-  const float nk = anchor_norm >= 0.f ? anchor_norm : sqrtf(kk);
+  dot = quad_swap_add<0xB1>(dot); qq = quad_swap_add<0xB1>(qq);   // quad_perm [1,0,3,2]
+  dot = quad_swap_add<0x4E>(dot); qq = quad_swap_add<0x4E>(qq);   // quad_perm [2,3,0,1]
+  const float nk = anchor_norm >= 0.f ? anchor_norm : sqrtf(quad_sumsq(kw));
   const float den = sqrtf(qq) * nk;
   return (den > 0.f) ? dot / den : 0.f;
 }
@@ -145,7 +168,8 @@ __device__ __forceinline__ bool route_decide(const float* cosines, int G, int L,
 // Standalone probe.  grid = B*H_kv, block = 64: 4 lanes per head, up to 16 heads.
 struct ProbeArgs {
   const uint4* q;
-  const uint4* k;
+  const void* k;
+  const void* k0;          // optional separate anchors
   const int32_t* seq_lens;
   const float* k0_norm;    // optional
   float* group_score;      // optional
@@ -160,7 +184,7 @@ __global__ __launch_bounds__(64) void sr_probe_kernel(ProbeArgs a) {
   const int b = bg / a.Hkv, g = bg - b * a.Hkv;
   const int lane4 = threadIdx.x & 3, i = threadIdx.x >> 2;
   const int hd = i < a.G ? i : 0;
-  const uint4* krow = a.k + (size_t)bg * a.Lmax * (kD / 8);                  // row 0 of the group's keys
+  const uint4* krow = anchor_row(a.k, a.k0, bg, a.Lmax);
   const uint4* qrow = a.q + ((size_t)b * a.Hq + (size_t)g * a.G + hd) * (kD / 8);
   uint4 qw[4], kw[4];
 #pragma unroll
@@ -176,6 +200,28 @@ __global__ __launch_bounds__(64) void sr_probe_kernel(ProbeArgs a) {
   }
 }
 
+// Prefill-side anchor caching (Section 4.1): copies row 0 of every group's key cache to
+// k0_out [B,H_kv,D] and its norm to k0_norm_out [B,H_kv].  One quad per group; the norm is computed
+// exactly as the probe recomputes it, so decisions do not depend on which of the two is used.
+__global__ __launch_bounds__(64) void sr_anchor_kernel(const void* k_cache, uint4* k0_out, float* k0_norm_out, int NG, int Lmax) {
+  const int lane4 = threadIdx.x & 3;
+  int bg = blockIdx.x * 16 + (threadIdx.x >> 2);
+  const bool ok = bg < NG;
+  bg = ok ? bg : NG - 1;
+  const uint4* krow = anchor_row(k_cache, nullptr, bg, Lmax);
+  uint4 kw[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) kw[j] = krow[lane4 + 4 * j];
+  const float kk = quad_sumsq(kw);
+  if (ok) {
+    if (k0_out) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) k0_out[(size_t)bg * (kD / 8) + lane4 + 4 * j] = kw[j];
+    }
+    if (k0_norm_out && lane4 == 0) k0_norm_out[bg] = sqrtf(kk);
+  }
+}
+
 // ------------------------------------------------------------------------------------------
 // Split-K partial attention.
 // ------------------------------------------------------------------------------------------
@@ -185,6 +231,7 @@ struct PartialArgs {
   const uint16_t* v;
   const int32_t* seq_lens;
   uint8_t* mask;    // [B*Hkv] read (written first when the probe is fused)
+  const void* k0;         // fused probe: optional separate anchors [B,H_kv,D]
   const float* k0_norm;   // fused probe: optional cached ||K_0||
   float* group_score;     // fused probe: S_g out
   RouteRule rule;         // fused probe
@@ -477,7 +524,6 @@ __global__ __launch_bounds__(kThreads, 2) void sr_partial_balanced_kernel(Partia
   if (kFused && a.rule.routing) {
     const int NH = NG * G, lane4 = tid & 3;
     const uint4* q4 = reinterpret_cast<const uint4*>(a.q);
-    const uint4* k4 = reinterpret_cast<const uint4*>(a.k);
     for (int h0 = 0; h0 < NH; h0 += kThreads / 2) {      // kThreads/4 heads per sweep, two sweeps in flight
       uint4 qw[2][4], kw[2][4];
       float kn[2];
@@ -487,7 +533,7 @@ __global__ __launch_bounds__(kThreads, 2) void sr_partial_balanced_kernel(Partia
         hd = hd < NH ? hd : NH - 1;
         const int i = hd / G;
         const uint4* qrow = q4 + (size_t)hd * (kD / 8);
-        const uint4* krow = k4 + (size_t)i * a.Lmax * (kD / 8);
+        const uint4* krow = anchor_row(a.k, a.k0, i, a.Lmax);
 #pragma unroll
         for (int j = 0; j < 4; ++j) { qw[u][j] = qrow[lane4 + 4 * j]; kw[u][j] = krow[lane4 + 4 * j]; }
         kn[u] = a.k0_norm ? a.k0_norm[i] : -1.f;
@@ -571,6 +617,12 @@ struct CombineArgs {
   const int32_t* sched;   // balanced schedule, else NULL
   uint32_t* out;          // bf16 pairs
   int Hq, Hkv, G, Lmax, chunk, slots;
+  // diagnostics (optional): log-sum-exp of the scaled scores and softmax mass on token 0 per head
+  const uint32_t* q;      // bf16 pairs
+  const void* k;
+  float* lse_out;
+  float* alpha0_out;
+  float scale_log2;
 };
 
 __global__ __launch_bounds__(kCombineThreads) void sr_combine_kernel(CombineArgs a) {
@@ -593,6 +645,10 @@ __global__ __launch_bounds__(kCombineThreads) void sr_combine_kernel(CombineArgs
   }
   if (n == 0) {                                  // zero surrogate (Eq. 11) / empty sequence
     if (wave == 0) orow[lane] = 0u;
+    if (threadIdx.x == 0) {                      // not computed for Sink Groups; an empty row has lse = -inf
+      if (a.lse_out) a.lse_out[bh] = (L == 0) ? -INFINITY : __int_as_float(0x7fc00000);
+      if (a.alpha0_out) a.alpha0_out[bh] = __int_as_float(0x7fc00000);
+    }
     return;
   }
   const float2* ml = reinterpret_cast<const float2*>(a.part_ml) + (size_t)bh * a.slots;
@@ -640,6 +696,18 @@ __global__ __launch_bounds__(kCombineThreads) void sr_combine_kernel(CombineArgs
     for (int u = 1; u < NW; ++u) { t.x += red_o[u][lane].x; t.y += red_o[u][lane].y; l += red_l[u]; }
     const float inv = 1.0f / l;
     orow[lane] = f32_to_bf16_rne(t.x * inv) | (f32_to_bf16_rne(t.y * inv) << 16);
+    if (a.lse_out || a.alpha0_out) {
+      const float lse2 = M + __builtin_amdgcn_logf(l);                  // log2 domain (v_log_f32 is log2)
+      if (a.alpha0_out) {                                               // alpha_0 = exp(z_0 - lse), Section 4.2
+        const uint32_t qw = a.q[(size_t)bh * (kD / 2) + lane];
+        const uint32_t kw = reinterpret_cast<const uint32_t*>(anchor_row(a.k, nullptr, bg, a.Lmax))[lane];   // token 0 of the cache itself
+        float d = bf16_lo(qw) * bf16_lo(kw) + bf16_hi(qw) * bf16_hi(kw);
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) d += __shfl_xor(d, o, 64);
+        if (lane == 0) a.alpha0_out[bh] = __builtin_amdgcn_exp2f(d * a.scale_log2 - lse2);
+      }
+      if (a.lse_out && lane == 0) a.lse_out[bh] = lse2 * 0.6931471805599453f;
+    }
   }
 }
 
@@ -750,7 +818,8 @@ int launch_probe(const void* q, const void* k, const int32_t* seq_lens, const sr
                  const Layout& lay, float* score, uint8_t* mask, hipStream_t st) {
   ProbeArgs a;
   a.q = static_cast<const uint4*>(q);
-  a.k = static_cast<const uint4*>(k);
+  a.k = k;
+  a.k0 = p->k0;
   a.seq_lens = seq_lens;
   a.k0_norm = p->k0_norm;
   a.group_score = score;
@@ -762,12 +831,14 @@ int launch_probe(const void* q, const void* k, const int32_t* seq_lens, const sr
 }
 
 int decode_impl(const void* q, const void* k, const void* v, const int32_t* seq_lens,
-                const sr_route_params* p, void* out, uint8_t* mask, float* stage_us) {
+                const sr_route_params* p, void* out, uint8_t* mask, float* stage_us,
+                float* lse_out = nullptr, float* alpha0_out = nullptr) {
   if (!q || !k || !v || !seq_lens || !p || !out || !mask) return SR_ERR_NULL;
   Layout lay;
   int rc = make_layout(p, &lay);
   if (rc != SR_OK) return rc;
-  if (misaligned(q, 16) || misaligned(k, 16) || misaligned(v, 16) || misaligned(out, 16) || misaligned(seq_lens, 4))
+  if (misaligned(q, 16) || misaligned(k, 16) || misaligned(v, 16) || misaligned(out, 16) || misaligned(seq_lens, 4) ||
+      misaligned(p->k0, 16) || misaligned(p->k0_norm, 4) || misaligned(lse_out, 4) || misaligned(alpha0_out, 4))
     return SR_ERR_ALIGN;
   if (!p->workspace || misaligned(p->workspace, 256) || p->workspace_bytes < lay.plan.workspace_bytes)
     return SR_ERR_WORKSPACE;
@@ -798,7 +869,7 @@ int decode_impl(const void* q, const void* k, const void* v, const int32_t* seq_
     a.k = static_cast<const uint16_t*>(k);
     a.v = static_cast<const uint16_t*>(v);
     a.seq_lens = seq_lens; a.mask = mask; a.part_o = part_o; a.part_ml = part_ml; a.sched = sched;
-    a.k0_norm = p->k0_norm; a.group_score = score; a.rule = make_rule(p);
+    a.k0 = p->k0; a.k0_norm = p->k0_norm; a.group_score = score; a.rule = make_rule(p);
 #if SR_TIMELINE
     a.timeline = reinterpret_cast<long long*>(ws + lay.plan.workspace_bytes - (size_t)kBalancedGrid * 8 * sizeof(long long));
 #endif
@@ -815,9 +886,12 @@ int decode_impl(const void* q, const void* k, const void* v, const int32_t* seq_
       hipLaunchKernelGGL(sr_partial_fixed_kernel, dim3(lay.plan.num_splits, a.NG), dim3(64 * kWaves), 0, st, a);
     ok = hipGetLastError() == hipSuccess;
   }
+  const float scale_log2 = (p->sm_scale > 0.f ? p->sm_scale : 0.08838834764831845f) * 1.4426950408889634f;
   if (ok) ok = mark(2);
   if (ok) {
     CombineArgs c;
+    c.q = static_cast<const uint32_t*>(q); c.k = k;
+    c.lse_out = lse_out; c.alpha0_out = alpha0_out; c.scale_log2 = scale_log2;
     c.part_o = part_o; c.part_ml = part_ml; c.seq_lens = seq_lens; c.mask = mask;
     c.sched = balanced ? sched : nullptr;
     c.out = static_cast<uint32_t*>(out);
@@ -881,10 +955,30 @@ int sinkrouter_probe(const void* q, const void* k_cache, const int32_t* seq_lens
   Layout lay;
   const int rc = make_layout(params, &lay);
   if (rc != SR_OK) return rc;
-  if (misaligned(q, 16) || misaligned(k_cache, 16) || misaligned(seq_lens, 4) || misaligned(group_score_out, 4))
+  if (misaligned(q, 16) || misaligned(k_cache, 16) || misaligned(seq_lens, 4) || misaligned(group_score_out, 4) ||
+      misaligned(params->k0, 16) || misaligned(params->k0_norm, 4))
     return SR_ERR_ALIGN;
   return launch_probe(q, k_cache, seq_lens, params, lay, group_score_out, skip_mask_out,
                       static_cast<hipStream_t>(params->stream));
+}
+
+int sinkrouter_decode_diag(const void* q, const void* k_cache, const void* v_cache, const int32_t* seq_lens,
+                           const sr_route_params* params, void* out, uint8_t* skip_mask_out,
+                           float* lse_out, float* alpha0_out) {
+  if (!lse_out && !alpha0_out) return SR_ERR_NULL;
+  return decode_impl(q, k_cache, v_cache, seq_lens, params, out, skip_mask_out, nullptr, lse_out, alpha0_out);
+}
+
+int sinkrouter_extract_anchor(const void* k_cache, const sr_route_params* params, void* k0_out, float* k0_norm_out) {
+  if (!k_cache || !params || (!k0_out && !k0_norm_out)) return SR_ERR_NULL;
+  Layout lay;
+  const int rc = make_layout(params, &lay);
+  if (rc != SR_OK) return rc;
+  if (misaligned(k_cache, 16) || misaligned(k0_out, 16) || misaligned(k0_norm_out, 4)) return SR_ERR_ALIGN;
+  const int NG = params->batch * params->n_kv_heads;
+  hipLaunchKernelGGL(sr_anchor_kernel, dim3((NG + 15) / 16), dim3(64), 0, static_cast<hipStream_t>(params->stream),
+                     k_cache, static_cast<uint4*>(k0_out), k0_norm_out, NG, params->max_seq_len);
+  return hipGetLastError() == hipSuccess ? SR_OK : SR_ERR_HIP;
 }
 
 int sinkrouter_hbm_read_probe(const void* buf, size_t bytes, void* sink, void* stream) {

@@ -18,17 +18,17 @@ def to_dev(a):
 
 
 def run_hip(q, k, v, seq_lens, *, tau_coef=(0, 0, 0, 0.55), len_norm=0.0, sm_scale=0.0,
-            routing_enabled=True, num_splits=0, k0_norm=None, dev=None, profiled=False):
+            routing_enabled=True, num_splits=0, k0_norm=None, dev=None, profiled=False, k0=None, k0_norm_dev=None):
     """One decode step on the GPU. Returns dict(out fp32 [B,Hq,D], mask uint8 [B,Hkv], score fp32, plan)."""
     import torch
     B, Hq, D = q.shape
     Hkv, Lmax = k.shape[1], k.shape[2]
     if dev is None:
         dev = dict(q=to_dev(q), k=to_dev(k), v=to_dev(v), sl=to_dev(np.asarray(seq_lens, np.int32)))
-    kn = None if k0_norm is None else to_dev(np.asarray(k0_norm, np.float32))
+    kn = k0_norm_dev if k0_norm is None else to_dev(np.asarray(k0_norm, np.float32))
     p = binding.make_route_params(B, Hq, Hkv, Lmax, head_dim=D, num_splits=num_splits,
                                   routing_enabled=routing_enabled, sm_scale=sm_scale,
-                                  tau_coef=tau_coef, len_norm=len_norm, k0_norm=kn)
+                                  tau_coef=tau_coef, len_norm=len_norm, k0_norm=kn, k0=k0)
     plan = binding.sinkrouter_plan(p)
     ws = torch.empty((plan.workspace_bytes,), dtype=torch.uint8, device="cuda")
     ws.fill_(0xFF)      # NaN pattern: an unwritten partial slot that gets read shows up

@@ -340,6 +340,36 @@ def check_symmetries(lib=None):
     assert not np.allclose(sw.out, base.dense_out)
 
 
+def check_separate_anchor(lib=None):
+    """Anchors kept apart from the cache (the K_0 tensor of Section 4.3) drive routing only."""
+    B, Hq, Hkv, D, L = 2, 8, 4, 8, 11
+    q, k, v, sl = synth.random_small(800, B, Hq, Hkv, D, L, [L, 7])
+    tau = (0, 0, 0, 0.0)
+    base = oracle.decode(q, k, v, sl, tau_coef=tau, want_dense=True, libpath=lib)
+    same = oracle.decode(q, k, v, sl, tau_coef=tau, want_dense=True, k0=k[:, :, 0].copy(), libpath=lib)
+    np.testing.assert_array_equal(same.group_score, base.group_score)
+    np.testing.assert_array_equal(same.out, base.out)
+    # other anchors: routing as if they were row 0, attention still over the real cache
+    rng = np.random.default_rng(5)
+    k0 = synth.f32_to_bf16_bits(rng.standard_normal((B, Hkv, D)).astype(np.float32))
+    alt = oracle.decode(q, k, v, sl, tau_coef=tau, want_dense=True, k0=k0, libpath=lib)
+    k_swapped = k.copy()
+    k_swapped[:, :, 0] = k0
+    ref_route = oracle.route(q, k_swapped, sl, tau_coef=tau, libpath=lib)
+    np.testing.assert_array_equal(alt.group_score, ref_route.group_score)
+    np.testing.assert_array_equal(alt.mask, ref_route.mask)
+    assert not np.array_equal(alt.group_score, base.group_score)
+    assert len({tuple(x) for x in alt.group_score.reshape(-1, 1).round(12).tolist()}) == B * Hkv   # one anchor per group
+    np.testing.assert_array_equal(alt.dense_out, base.dense_out)
+    out, _, _ = library_attention(q, k, v, sl)
+    keep = np.repeat(1 - alt.mask, Hq // Hkv, axis=1)[..., None]
+    np.testing.assert_allclose(alt.out, out * keep, rtol=1e-12, atol=1e-13)
+    # same through the Split-K entry and the route-only entry
+    o2, m2, _, _ = oracle.decode_splitk(q, k, v, sl, [0, 4, L], tau_coef=tau, k0=k0, libpath=lib)
+    np.testing.assert_array_equal(m2, alt.mask)
+    np.testing.assert_allclose(o2, alt.out, rtol=1e-12, atol=1e-13)
+
+
 ALL_PINS = [check_golden, check_brute_force_dense, check_routed_vs_library,
             check_splitk_equals_single_pass, check_closed_forms, check_cosine_properties,
-            check_decision_properties, check_skip_error_bound, check_symmetries]
+            check_decision_properties, check_skip_error_bound, check_symmetries, check_separate_anchor]

@@ -22,10 +22,10 @@ def declared_functions():
 def test_library_exports_every_declared_symbol():
     lib = B.load()
     names = declared_functions()
-    assert len(names) >= 9
+    assert len(names) >= 11
     for n in names:
         assert hasattr(lib, n), "libsinkrouter.so does not export %s" % n
-    assert B.sinkrouter_abi_version() == 1
+    assert B.sinkrouter_abi_version() == 2
 
 
 def test_binding_mirrors_header_structs():

@@ -38,8 +38,11 @@ MUTANTS = [
     ("alpha0_is_last_token", "exp(z[0] - m) / l", "exp(z[L - 1] - m) / l"),
     ("lse_drops_max", "m + log(l)", "log(l)"),
     ("zero_length_still_routed", "c->routing_enabled && L > 0 &&", "c->routing_enabled &&"),
-    ("anchor_is_last_row", "const uint16_t* k0 = k_cache + ((size_t)b * Hkv + g) * (size_t)c->max_seq_len * D;",
-     "const uint16_t* k0 = k_cache + ((size_t)b * Hkv + g) * (size_t)c->max_seq_len * D + (size_t)(L > 0 ? L - 1 : 0) * D;"),
+    ("anchor_is_last_row", ": k_cache + ((size_t)b * Hkv + g) * (size_t)c->max_seq_len * D;",
+     ": k_cache + ((size_t)b * Hkv + g) * (size_t)c->max_seq_len * D + (size_t)(L > 0 ? L - 1 : 0) * D;"),
+    ("separate_anchor_ignored", "const uint16_t* k0 = k0_rows ? k0_rows + ((size_t)b * Hkv + g) * D",
+     "const uint16_t* k0 = (0 && k0_rows) ? k0_rows + ((size_t)b * Hkv + g) * D"),
+    ("separate_anchor_wrong_group", "k0_rows + ((size_t)b * Hkv + g) * D", "k0_rows + ((size_t)b * Hkv) * D"),
 ]
 
 
