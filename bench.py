@@ -82,7 +82,7 @@ def time_steps(fn, steps, warmup):
     return (time.perf_counter() - t0) / steps * 1e6
 
 
-def run_workload(name, steps, warmup, copies, verbose, num_splits=0):
+def run_workload(name, steps, warmup, copies, verbose, num_splits=0, page_tokens=0):
     import torch
     from paper_2604_16883_amd import binding, synth
     w = synth.WORKLOADS[name]
@@ -91,8 +91,18 @@ def run_workload(name, steps, warmup, copies, verbose, num_splits=0):
     gen_s = time.time() - t0
     tq = torch.from_numpy(sb.q.view(np.int16)).cuda()
     tsl = torch.from_numpy(sb.seq_lens).cuda()
-    k0 = torch.from_numpy(sb.k.view(np.int16)).cuda()
-    v0 = torch.from_numpy(sb.v.view(np.int16)).cuda()
+    layout = table = None
+    if page_tokens:
+        # the same cache scattered into a page pool in a seeded random page order
+        kp, tab = synth.to_pages(sb.k, sb.seq_lens, page_tokens, seed=w.base_seed)
+        vp, _ = synth.to_pages(sb.v, sb.seq_lens, page_tokens, seed=w.base_seed)
+        k0, v0 = torch.from_numpy(kp.view(np.int16)).cuda(), torch.from_numpy(vp.view(np.int16)).cuda()
+        table = torch.from_numpy(tab).cuda()
+        layout = binding.make_paged_layout(page_tokens, tab.shape[1], kp.shape[0])
+        del kp, vp
+    else:
+        k0 = torch.from_numpy(sb.k.view(np.int16)).cuda()
+        v0 = torch.from_numpy(sb.v.view(np.int16)).cuda()
     # rotate over distinct copies so that no step finds its K/V in the last-level cache
     ks = [k0] + [k0.clone() for _ in range(copies - 1)]
     vs = [v0] + [v0.clone() for _ in range(copies - 1)]
@@ -112,14 +122,20 @@ def run_workload(name, steps, warmup, copies, verbose, num_splits=0):
         def step():
             i = it[0] % copies
             it[0] += 1
-            binding.sinkrouter_decode(tq, ks[i], vs[i], tsl, p, out, mask)
+            if layout is None:
+                binding.sinkrouter_decode(tq, ks[i], vs[i], tsl, p, out, mask)
+            else:
+                binding.sinkrouter_decode_paged(tq, ks[i], vs[i], table, tsl, p, layout, out, mask)
 
         us = time_steps(step, steps, warmup)
         # per-kernel durations from HIP events on the launch stream, same rotation
         st = np.zeros((steps, 4))
         for s in range(steps):
             i = s % copies
-            st[s] = binding.sinkrouter_decode_profiled(tq, ks[i], vs[i], tsl, p, out, mask)
+            if layout is None:
+                st[s] = binding.sinkrouter_decode_profiled(tq, ks[i], vs[i], tsl, p, out, mask)
+            else:       # no per-kernel events for the paged entry point: whole step only
+                st[s] = (0.0, us, 0.0, us)
         torch.cuda.synchronize()
         m = mask.cpu().numpy()
         ab = algorithmic_bytes(w, sb.seq_lens, m, plan)
@@ -135,7 +151,7 @@ def run_workload(name, steps, warmup, copies, verbose, num_splits=0):
             "algorithmic_bytes": int(ab),
             "partial_GBps": round(ab / partial_us / 1e3, 1),
             "step_GBps": round(ab / us / 1e3, 1),
-            "schedule": "balanced" if plan.schedule else "fixed",
+            "schedule": "balanced" if plan.schedule else "fixed", "page_tokens": page_tokens,
             "partial_grid": int(plan.partial_grid), "partial_records": partial_records(w, sb.seq_lens, m, plan),
         }
         res[label] = r
@@ -199,6 +215,8 @@ def main():
     ap.add_argument("--copies", type=int, default=3, help="distinct K/V copies rotated through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--num-splits", type=int, default=0, help="0 = balanced schedule, >0 = fixed Split-K chunks")
+    ap.add_argument("--paged", type=int, default=0, metavar="PAGE_TOKENS",
+                    help="run over a paged KV cache with this page size (power of two >= 64); 0 = contiguous")
     ap.add_argument("-v", "--verbose", action="store_true")
     a = ap.parse_args()
     if a.gpus != 1:
@@ -213,13 +231,13 @@ def main():
     binding.load()
 
     calib = hbm_calibration()
-    main_res, sb, _dev = run_workload(a.workload, a.steps, a.warmup, a.copies, a.verbose, a.num_splits)
+    main_res, sb, _dev = run_workload(a.workload, a.steps, a.warmup, a.copies, a.verbose, a.num_splits, a.paged)
     cpu = None if a.no_cpu_baseline else cpu_baseline(sb)
     del _dev
     torch.cuda.empty_cache()
     others = {}
     for name in [x for x in a.also.split(",") if x and x != a.workload]:
-        r, sb2, dev2 = run_workload(name, a.steps, a.warmup, max(a.copies, 4), a.verbose, a.num_splits)
+        r, sb2, dev2 = run_workload(name, a.steps, a.warmup, max(a.copies, 4), a.verbose, a.num_splits, a.paged)
         others[name] = r
         del sb2, dev2
         torch.cuda.empty_cache()
@@ -239,7 +257,7 @@ def main():
                    "schedule": routed["schedule"], "partial_grid": routed["partial_grid"]},
         "roofline": {"bound": "hbm", "kernel": "sr_partial_balanced_kernel (routing probe fused)", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(a.workload) if a.num_splits == 0 else None,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(a.workload) if a.num_splits == 0 and not a.paged else None,
                      "algorithmic_bytes_per_launch": routed["algorithmic_bytes"],
                      "kernel_us": routed["partial_us"],
                      "dense_achieved": main_res["dense"]["partial_GBps"],

@@ -160,6 +160,33 @@ int sinkrouter_decode_diag(const void* q, const void* k_cache, const void* v_cac
                            void* out, uint8_t* skip_mask_out, float* lse_out, float* alpha0_out);
 
 /*
+ * Paged KV cache (serving layout; the paper's kernel takes contiguous caches, Section 4.3).
+ * Pages hold page_tokens tokens, a power of two >= 64, so a 64-token block never straddles a
+ * page; the pools are laid out [n_pages, H_kv, page_tokens, D] bf16.
+ */
+typedef struct sr_paged_layout {
+  uint32_t struct_size;     /* sizeof(sr_paged_layout) */
+  int32_t page_tokens;      /* tokens per page: 64, 128, 256, ... */
+  int32_t pages_per_seq;    /* row stride of block_table; pages_per_seq * page_tokens >= max_seq_len */
+  int32_t n_pages;          /* pages in the pools; table entries are clamped to [0, n_pages) on the device */
+} sr_paged_layout;
+
+/*
+ * sinkrouter_decode over a paged cache: identical result to sinkrouter_decode on the cache that
+ * gathering the pages would give.
+ *   k_pages, v_pages device bf16 [n_pages,H_kv,page_tokens,D]
+ *   block_table      device int32 [B,pages_per_seq]: physical page of each logical page; only
+ *                    entries below ceil(seq_lens[b] / page_tokens) are read
+ * params->max_seq_len bounds the sequence lengths (they are clamped to it); params->k0 and
+ * params->k0_norm work as for the contiguous entry point.  Token 0 is the first token of the
+ * page block_table[b][0].
+ */
+int sinkrouter_decode_paged(const void* q, const void* k_pages, const void* v_pages,
+                            const int32_t* block_table, const int32_t* seq_lens,
+                            const sr_route_params* params, const sr_paged_layout* layout,
+                            void* out, uint8_t* skip_mask_out);
+
+/*
  * Prefill-side anchor caching (Section 4.1): copies row 0 of every (sequence, KV group) key cache
  * to k0_out (device bf16 [B,H_kv,D], optional) and writes its Euclidean norm to k0_norm_out
  * (device fp32 [B,H_kv], optional); at least one must be given.  The norm is computed exactly as

@@ -233,3 +233,31 @@ def decode_splitk(q, k_cache, v_cache, seq_lens, bounds, *, tau_coef=(0.0, 0.0, 
     if rc != 0:
         raise RuntimeError("sr_oracle_decode_splitk failed: %d" % rc)
     return out, mask, pm, pl
+
+
+def gather_pages(pages, block_table, seq_lens, max_seq_len: int, libpath: Optional[str] = None) -> np.ndarray:
+    """Paged pool [n_pages,Hkv,page_tokens,D] + block_table [B,pages_per_seq] -> contiguous cache
+    [B,Hkv,max_seq_len,D] (rows beyond seq_lens[b] are zero)."""
+    lib = _load(libpath)
+    pages = np.ascontiguousarray(pages)
+    n_pages, Hkv, pt, D = pages.shape
+    pages = _u16(pages, pages.shape)
+    tab = np.ascontiguousarray(np.asarray(block_table, dtype=np.int32))
+    B, pps = tab.shape
+    sl = np.ascontiguousarray(np.asarray(seq_lens, dtype=np.int32))
+    cache = np.empty((B, Hkv, int(max_seq_len), D), np.uint16)
+    rc = lib.sr_oracle_gather_pages(_ptr(pages, ctypes.c_uint16), _ptr(tab, ctypes.c_int32), _ptr(sl, ctypes.c_int32),
+                                    ctypes.c_int32(B), ctypes.c_int32(Hkv), ctypes.c_int32(D), ctypes.c_int32(int(max_seq_len)),
+                                    ctypes.c_int32(pt), ctypes.c_int32(pps), ctypes.c_int32(n_pages),
+                                    _ptr(cache, ctypes.c_uint16))
+    if rc != 0:
+        raise RuntimeError("sr_oracle_gather_pages failed: %d" % rc)
+    return cache
+
+
+def decode_paged(q, k_pages, v_pages, block_table, seq_lens, max_seq_len: int, **kw) -> OracleResult:
+    """Routed decode over a paged cache: the decode step on the gathered contiguous cache."""
+    lib = kw.get("libpath")
+    k = gather_pages(k_pages, block_table, seq_lens, max_seq_len, libpath=lib)
+    v = gather_pages(v_pages, block_table, seq_lens, max_seq_len, libpath=lib)
+    return decode(q, k, v, seq_lens, **kw)

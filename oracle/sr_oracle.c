@@ -312,6 +312,34 @@ int sr_oracle_decode_splitk(const uint16_t* q, const uint16_t* k_cache, const ui
   return failed ? -3 : 0;
 }
 
+/*
+ * Paged cache -> contiguous cache.  pages is [n_pages, H_kv, page_tokens, D]; logical page j of
+ * sequence b is physical page table[b * pages_per_seq + j]; token t of (b, g) is therefore row
+ * t % page_tokens of group g of page table[b][t / page_tokens].  Fills cache [B, H_kv, L_max, D]
+ * for t < seq_lens[b] and leaves the other rows zero.  A paged decode step is, by definition, the
+ * decode step on this gathered cache (the paper's kernel takes contiguous caches, Section 4.3).
+ */
+int sr_oracle_gather_pages(const uint16_t* pages, const int32_t* table, const int32_t* seq_lens,
+                           int32_t B, int32_t Hkv, int32_t D, int32_t Lmax, int32_t page_tokens,
+                           int32_t pages_per_seq, int32_t n_pages, uint16_t* cache) {
+  if (!pages || !table || !seq_lens || !cache) return -1;
+  if (B < 1 || Hkv < 1 || D < 1 || Lmax < 1 || page_tokens < 1 || pages_per_seq < 1 || n_pages < 1) return -2;
+  memset(cache, 0, sizeof(uint16_t) * (size_t)B * Hkv * Lmax * D);
+  for (int b = 0; b < B; ++b) {
+    int32_t L = clamp_len(seq_lens[b], Lmax);
+    for (int g = 0; g < Hkv; ++g)
+      for (int32_t t = 0; t < L; ++t) {
+        int32_t j = t / page_tokens;
+        if (j >= pages_per_seq) return -2;
+        int32_t page = table[(size_t)b * pages_per_seq + j];
+        if (page < 0 || page >= n_pages) return -4;
+        const uint16_t* src = pages + (((size_t)page * Hkv + g) * page_tokens + (t % page_tokens)) * D;
+        memcpy(cache + (((size_t)b * Hkv + g) * Lmax + t) * D, src, sizeof(uint16_t) * D);
+      }
+  }
+  return 0;
+}
+
 int sr_oracle_threads(void) {
 #ifdef _OPENMP
   return omp_get_max_threads();

@@ -48,6 +48,16 @@ class RouteParams(ctypes.Structure):
     ]
 
 
+class PagedLayout(ctypes.Structure):
+    """Mirror of ``sr_paged_layout``."""
+    _fields_ = [
+        ("struct_size", ctypes.c_uint32),
+        ("page_tokens", ctypes.c_int32),
+        ("pages_per_seq", ctypes.c_int32),
+        ("n_pages", ctypes.c_int32),
+    ]
+
+
 class Plan(ctypes.Structure):
     """Mirror of ``sr_plan``."""
     _fields_ = [
@@ -91,6 +101,8 @@ def load() -> ctypes.CDLL:
         lib.sinkrouter_decode_profiled.restype = ctypes.c_int
         lib.sinkrouter_decode_diag.argtypes = [vp, vp, vp, i32p, pp, vp, vp, vp, vp]
         lib.sinkrouter_decode_diag.restype = ctypes.c_int
+        lib.sinkrouter_decode_paged.argtypes = [vp, vp, vp, vp, i32p, pp, ctypes.POINTER(PagedLayout), vp, vp]
+        lib.sinkrouter_decode_paged.restype = ctypes.c_int
         lib.sinkrouter_extract_anchor.argtypes = [vp, pp, vp, vp]
         lib.sinkrouter_extract_anchor.restype = ctypes.c_int
         lib.sinkrouter_probe.argtypes = [vp, vp, i32p, pp, vp, vp]
@@ -210,6 +222,24 @@ def sinkrouter_decode_diag(q, k_cache, v_cache, seq_lens, route_params: RoutePar
                                        _addr(out), _addr(skip_mask_out), _addr(lse_out), _addr(alpha0_out))
     if check and rc != SR_OK:
         raise SinkRouterError(rc, "sinkrouter_decode_diag")
+    return rc
+
+
+def make_paged_layout(page_tokens: int, pages_per_seq: int, n_pages: int) -> PagedLayout:
+    lay = PagedLayout()
+    lay.struct_size = ctypes.sizeof(PagedLayout)
+    lay.page_tokens, lay.pages_per_seq, lay.n_pages = int(page_tokens), int(pages_per_seq), int(n_pages)
+    return lay
+
+
+def sinkrouter_decode_paged(q, k_pages, v_pages, block_table, seq_lens, route_params: RouteParams,
+                            layout: PagedLayout, out, skip_mask_out, check: bool = True) -> int:
+    """One routed decode step over a paged KV cache; asynchronous."""
+    p = _with_stream(route_params)
+    rc = load().sinkrouter_decode_paged(_addr(q), _addr(k_pages), _addr(v_pages), _addr(block_table), _addr(seq_lens),
+                                        ctypes.byref(p), ctypes.byref(layout), _addr(out), _addr(skip_mask_out))
+    if check and rc != SR_OK:
+        raise SinkRouterError(rc, "sinkrouter_decode_paged")
     return rc
 
 

@@ -16,6 +16,8 @@ HIPCC_FLAGS = [
     # keep the compiler from forming packed-fp32 VALU instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-command-line-argument",
+    # one remark block per kernel with its register, LDS and scratch use (checked below)
+    "-Rpass-analysis=kernel-resource-usage",
 ]
 
 
@@ -33,10 +35,45 @@ def build_library(verbose: bool = False, extra=()) -> str:
         if os.path.exists(tmp):
             os.remove(tmp)
         raise RuntimeError("hipcc failed:\n" + log)
+    usage = kernel_resource_usage(log)
+    import re
+    keep, skip = [], 0
+    for l in log.splitlines():          # drop the remarks and the two source-echo lines after each
+        if "[-Rpass-analysis=kernel-resource-usage]" in l:
+            skip = 2
+        elif skip and re.match(r"^\s+(\d+ )?\|", l):
+            skip -= 1
+        else:
+            skip = 0
+            keep.append(l)
+    log = "\n".join(keep)
     if verbose and log.strip():
         print(log)
+    if verbose:
+        for name, u in sorted(usage.items()):
+            print("  %-60s VGPRs %3s  LDS %6s B  scratch %s B/lane" % (name[:60], u.get("VGPRs"), u.get("LDS Size [bytes/block]"),
+                                                                      u.get("ScratchSize [bytes/lane]")))
+    spilled = [n for n, u in usage.items() if int(u.get("ScratchSize [bytes/lane]", 0)) > 0]
+    if spilled:
+        os.remove(tmp)
+        raise RuntimeError("kernels spill registers to scratch memory: %s" % ", ".join(spilled))
     os.replace(tmp, LIB)
     return LIB
+
+
+def kernel_resource_usage(log: str) -> dict:
+    """Parse clang's kernel-resource-usage remarks: {kernel name: {field: value}}."""
+    import re
+    usage, cur = {}, None
+    for line in log.splitlines():
+        m = re.search(r"remark: Function Name: (\S+) \[-Rpass-analysis", line)
+        if m:
+            cur = usage.setdefault(m.group(1), {})
+            continue
+        m = re.search(r"remark:\s+([A-Za-z][^:]*): (\S+) \[-Rpass-analysis", line)
+        if m and cur is not None:
+            cur[m.group(1).strip()] = m.group(2)
+    return usage
 
 
 if __name__ == "__main__":

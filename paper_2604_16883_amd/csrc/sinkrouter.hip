@@ -91,11 +91,35 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
 
 __device__ __forceinline__ int clamp_len(int L, int Lmax) { return L < 0 ? 0 : (L > Lmax ? Lmax : L); }
 
+// Paged KV cache: pages of 2^page_shift tokens laid out [n_pages, H_kv, page_tokens, D]; logical
+// page j of sequence b is physical page table[b * pages_per_seq + j] (clamped to the pool, so a
+// bad entry reads a wrong page but never leaves the allocation).  table == NULL: contiguous cache.
+struct PageMap {
+  const int32_t* table;
+  int page_shift, pages_per_seq, n_pages;
+};
+
+__device__ __forceinline__ int page_of(const PageMap& pm, int b, int tok) {
+  int pg = pm.table[(size_t)b * pm.pages_per_seq + (tok >> pm.page_shift)];
+  pg = pg < 0 ? 0 : pg;
+  return pg < pm.n_pages ? pg : pm.n_pages - 1;
+}
+
+// Offset (in 16-byte units) of token `tok` of group g in a page pool, given its physical page.
+__device__ __forceinline__ size_t paged_offset(const PageMap& pm, int page, int Hkv, int g, int tok) {
+  return ((((size_t)page * Hkv + g) << pm.page_shift) + (tok & ((1 << pm.page_shift) - 1))) * (kD / 8);
+}
+
 // K_0 of (sequence, KV group) bg: row bg of the separately cached anchors [B,H_kv,D] when the caller
-// keeps them (Section 4.3 layout), else row 0 of the group's key cache.
-__device__ __forceinline__ const uint4* anchor_row(const void* k_cache, const void* k0, int bg, int Lmax) {
-  return k0 ? static_cast<const uint4*>(k0) + (size_t)bg * (kD / 8)
-            : static_cast<const uint4*>(k_cache) + (size_t)bg * Lmax * (kD / 8);
+// keeps them (Section 4.3 layout), else token 0 of the group's key cache.
+__device__ __forceinline__ const uint4* anchor_row(const void* k_cache, const void* k0, int bg, int Lmax, int Hkv,
+                                                   const PageMap& pm) {
+  if (k0) return static_cast<const uint4*>(k0) + (size_t)bg * (kD / 8);
+  if (pm.table) {
+    const int b = bg / Hkv, g = bg - b * Hkv;
+    return static_cast<const uint4*>(k_cache) + paged_offset(pm, page_of(pm, b, 0), Hkv, g, 0);
+  }
+  return static_cast<const uint4*>(k_cache) + (size_t)bg * Lmax * (kD / 8);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -176,6 +200,7 @@ struct ProbeArgs {
   uint8_t* mask;
   int Hq, Hkv, G, Lmax;
   RouteRule rule;
+  PageMap pm;
 };
 
 __global__ __launch_bounds__(64) void sr_probe_kernel(ProbeArgs a) {
@@ -184,7 +209,7 @@ __global__ __launch_bounds__(64) void sr_probe_kernel(ProbeArgs a) {
   const int b = bg / a.Hkv, g = bg - b * a.Hkv;
   const int lane4 = threadIdx.x & 3, i = threadIdx.x >> 2;
   const int hd = i < a.G ? i : 0;
-  const uint4* krow = anchor_row(a.k, a.k0, bg, a.Lmax);
+  const uint4* krow = anchor_row(a.k, a.k0, bg, a.Lmax, a.Hkv, a.pm);
   const uint4* qrow = a.q + ((size_t)b * a.Hq + (size_t)g * a.G + hd) * (kD / 8);
   uint4 qw[4], kw[4];
 #pragma unroll
@@ -203,12 +228,13 @@ __global__ __launch_bounds__(64) void sr_probe_kernel(ProbeArgs a) {
 // Prefill-side anchor caching (Section 4.1): copies row 0 of every group's key cache to
 // k0_out [B,H_kv,D] and its norm to k0_norm_out [B,H_kv].  One quad per group; the norm is computed
 // exactly as the probe recomputes it, so decisions do not depend on which of the two is used.
-__global__ __launch_bounds__(64) void sr_anchor_kernel(const void* k_cache, uint4* k0_out, float* k0_norm_out, int NG, int Lmax) {
+__global__ __launch_bounds__(64) void sr_anchor_kernel(const void* k_cache, uint4* k0_out, float* k0_norm_out, int NG, int Lmax,
+                                                       int Hkv, PageMap pm) {
   const int lane4 = threadIdx.x & 3;
   int bg = blockIdx.x * 16 + (threadIdx.x >> 2);
   const bool ok = bg < NG;
   bg = ok ? bg : NG - 1;
-  const uint4* krow = anchor_row(k_cache, nullptr, bg, Lmax);
+  const uint4* krow = anchor_row(k_cache, nullptr, bg, Lmax, Hkv, pm);
   uint4 kw[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) kw[j] = krow[lane4 + 4 * j];
@@ -242,33 +268,38 @@ struct PartialArgs {
   int chunk;        // fixed schedule: tokens per chunk
   int slots;        // partial records per head
   float scale_log2; // softmax scale * log2(e)
+  PageMap pm;
 #if SR_TIMELINE
   long long* timeline;
 #endif
 };
 
-// K tile T, step j: lane (r16, kg) holds token tok0+16T+r16, elements (4j+kg)*8 .. +8.
-// Rows are clamped to the last valid one, so a ragged tail never reads beyond seq_len.
+// Loads of one 64-token block whose first row is row0 of the slab at Kbase / Vbase (a contiguous
+// (sequence, group) cache, or one group's part of a page: a block never straddles a page).
+// row_last is the slab row of the last valid token of the sequence: rows are clamped to it, so a
+// ragged tail never reads beyond seq_len.
+//
+// K tile T, step j: lane (r16, kg) holds row row0+16T+r16, elements (4j+kg)*8 .. +8.
 // A row reaches the wavefront as 64-byte pieces, two loads per 128-byte line, so these stay
 // ordinary cached loads (the second piece of a line hits); a non-temporal hint here costs bandwidth.
-__device__ __forceinline__ void load_k_tile(uint4 (&kr)[4], const uint4* __restrict__ K4, int tok0, int T,
-                                            int r16, int kg, int last) {
-  int row = tok0 + 16 * T + r16;
-  row = row < last ? row : last;
-  const uint4* p = K4 + (size_t)row * 16 + kg;
+__device__ __forceinline__ void load_k_tile(uint4 (&kr)[4], const uint4* __restrict__ Kbase, int row0, int T,
+                                            int r16, int kg, int row_last) {
+  int row = row0 + 16 * T + r16;
+  row = row < row_last ? row : row_last;
+  const uint4* p = Kbase + (size_t)row * 16 + kg;
 #pragma unroll
   for (int j = 0; j < 4; ++j) kr[j] = p[4 * j];
 }
 
-// V tile T, row r: lane (r16, kg) holds token tok0+16T+4kg+r, elements 8*r16 .. +8: each load
+// V tile T, row r: lane (r16, kg) holds row row0+16T+4kg+r, elements 8*r16 .. +8: each load
 // instruction covers four whole 256-byte rows.
-__device__ __forceinline__ void load_v_tile(uint4 (&vr)[4], const uint4* __restrict__ V4, int tok0, int T,
-                                            int r16, int kg, int last) {
+__device__ __forceinline__ void load_v_tile(uint4 (&vr)[4], const uint4* __restrict__ Vbase, int row0, int T,
+                                            int r16, int kg, int row_last) {
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
-    int row = tok0 + 16 * T + 4 * kg + r;
-    row = row < last ? row : last;
-    vr[r] = load_stream(V4 + (size_t)row * 16 + r16);
+    int row = row0 + 16 * T + 4 * kg + r;
+    row = row < row_last ? row : row_last;
+    vr[r] = load_stream(Vbase + (size_t)row * 16 + r16);
   }
 }
 
@@ -285,9 +316,8 @@ struct WaveState {
 // read its registers (it would need a second register set) or sinking it to the end of the block.
 template <bool kPrefetch>
 __device__ __forceinline__ void block_step(WaveState& w, uint4 (&kr)[4][4], uint4 (&vr)[4][4], const bf16x8 (&qb)[4],
-                                           const uint4* __restrict__ K4, const uint4* __restrict__ V4,
-                                           int tok0, int next, int t_end, int last, int r16, int kg,
-                                           float scale_log2) {
+                                           const uint4* __restrict__ Kn, const uint4* __restrict__ Vn, int row0_n, int row_last_n,
+                                           int tok0, int t_end, int r16, int kg, float scale_log2) {
   // ---- scores: sc[T][r] = q_{r16} . k_{tok0+16T+4kg+r}
   f32x4 sc[4];
 #pragma unroll
@@ -298,7 +328,7 @@ __device__ __forceinline__ void block_step(WaveState& w, uint4 (&kr)[4][4], uint
       sc[T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kr[T][j]), qb[j], sc[T], 0, 0, 0);
 #if SR_FINE_PREFETCH
     __builtin_amdgcn_sched_barrier(0);
-    if (kPrefetch) load_k_tile(kr[T], K4, next, T, r16, kg, last);
+    if (kPrefetch) load_k_tile(kr[T], Kn, row0_n, T, r16, kg, row_last_n);
     __builtin_amdgcn_sched_barrier(0);
 #endif
   }
@@ -306,7 +336,7 @@ __device__ __forceinline__ void block_step(WaveState& w, uint4 (&kr)[4][4], uint
   __builtin_amdgcn_sched_barrier(0);
   if (kPrefetch) {
 #pragma unroll
-    for (int T = 0; T < 4; ++T) load_k_tile(kr[T], K4, next, T, r16, kg, last);
+    for (int T = 0; T < 4; ++T) load_k_tile(kr[T], Kn, row0_n, T, r16, kg, row_last_n);
   }
   __builtin_amdgcn_sched_barrier(0);
 #endif
@@ -383,7 +413,7 @@ __device__ __forceinline__ void block_step(WaveState& w, uint4 (&kr)[4][4], uint
     }
 #if SR_FINE_PREFETCH
     __builtin_amdgcn_sched_barrier(0);
-    if (kPrefetch) { load_v_tile(vr[T], V4, next, T, r16, kg, last); load_v_tile(vr[T + 1], V4, next, T + 1, r16, kg, last); }
+    if (kPrefetch) { load_v_tile(vr[T], Vn, row0_n, T, r16, kg, row_last_n); load_v_tile(vr[T + 1], Vn, row0_n, T + 1, r16, kg, row_last_n); }
     __builtin_amdgcn_sched_barrier(0);
 #endif
   }
@@ -391,7 +421,7 @@ __device__ __forceinline__ void block_step(WaveState& w, uint4 (&kr)[4][4], uint
   __builtin_amdgcn_sched_barrier(0);
   if (kPrefetch) {
 #pragma unroll
-    for (int T = 0; T < 4; ++T) load_v_tile(vr[T], V4, next, T, r16, kg, last);
+    for (int T = 0; T < 4; ++T) load_v_tile(vr[T], Vn, row0_n, T, r16, kg, row_last_n);
   }
   __builtin_amdgcn_sched_barrier(0);
 #endif
@@ -400,11 +430,13 @@ __device__ __forceinline__ void block_step(WaveState& w, uint4 (&kr)[4][4], uint
 // Attention of the G heads of group (b, g) over tokens [t_begin, t_end) (t_begin a multiple of 64,
 // t_begin < t_end <= L), by the whole workgroup; writes partial record `slot` of each head.
 // Every thread of the workgroup must call it (it synchronises).
+template <bool kPaged>
 __device__ __forceinline__ void attend_range(const PartialArgs& a, int b, int g, int L, int t_begin, int t_end, int slot) {
   __shared__ float lds_o[kWaves][kMaxGroup][kOStride];
   __shared__ float lds_m[kWaves][kMaxGroup];
   __shared__ float lds_l[kWaves][kMaxGroup];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int r16 = lane & 15, kg = lane >> 4;
   const int G = a.G;
   const int bg = b * a.Hkv + g;
@@ -422,8 +454,15 @@ __device__ __forceinline__ void attend_range(const PartialArgs& a, int b, int g,
       qb[j] = __builtin_bit_cast(bf16x8, x);
     }
   }
-  const uint4* K4 = reinterpret_cast<const uint4*>(a.k + (size_t)bg * a.Lmax * kD);
-  const uint4* V4 = reinterpret_cast<const uint4*>(a.v + (size_t)bg * a.Lmax * kD);
+  // Slab = the rows that share one base pointer: the whole (sequence, group) cache, or the group's
+  // part of one page.  slab_base(page) is its offset in 16-byte units, slab_row(tok) the row of a token.
+  const uint4* K4 = reinterpret_cast<const uint4*>(a.k);
+  const uint4* V4 = reinterpret_cast<const uint4*>(a.v);
+  const int page_mask = kPaged ? (1 << a.pm.page_shift) - 1 : 0;
+  auto slab_base = [&](int page) -> size_t {
+    return kPaged ? (((size_t)page * a.Hkv + g) << a.pm.page_shift) * (kD / 8) : (size_t)bg * a.Lmax * (kD / 8);
+  };
+  auto slab_row = [&](int tok) -> int { return kPaged ? (tok & page_mask) : tok; };
 
   WaveState w;
   w.m_run = -INFINITY;
@@ -431,26 +470,36 @@ __device__ __forceinline__ void attend_range(const PartialArgs& a, int b, int g,
 #pragma unroll
   for (int e = 0; e < 8; ++e) w.acc[e] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  int tok0 = t_begin + wave * kBlock;      // the 4 wavefronts interleave 64-token blocks
+  constexpr int kStep = kWaves * kBlock;   // the wavefronts of the workgroup interleave 64-token blocks
+  int tok0 = t_begin + wave * kBlock;
   if (tok0 < t_end) {
     uint4 kr[4][4], vr[4][4];
+    {
+      const size_t base = slab_base(kPaged ? page_of(a.pm, b, tok0) : 0);
+      const int row0 = slab_row(tok0), row_last = row0 + (last - tok0);
 #pragma unroll
-    for (int T = 0; T < 4; ++T) load_k_tile(kr[T], K4, tok0, T, r16, kg, last);
+      for (int T = 0; T < 4; ++T) load_k_tile(kr[T], K4 + base, row0, T, r16, kg, row_last);
 #pragma unroll
-    for (int T = 0; T < 4; ++T) load_v_tile(vr[T], V4, tok0, T, r16, kg, last);
-    int next = tok0 + kWaves * kBlock;
+      for (int T = 0; T < 4; ++T) load_v_tile(vr[T], V4 + base, row0, T, r16, kg, row_last);
+    }
+    int next = tok0 + kStep;
+    // paged: the page of a block is looked up one iteration before the block is prefetched
+    int page_n = (kPaged && next < t_end) ? page_of(a.pm, b, next) : 0;
 #if SR_TIMELINE
     bool first = true;
 #endif
     while (next < t_end) {
-      block_step<true>(w, kr, vr, qb, K4, V4, tok0, next, t_end, last, r16, kg, a.scale_log2);
+      const size_t base = slab_base(page_n);
+      const int row0 = slab_row(next), row_last = row0 + (last - next);
+      if (kPaged) page_n = page_of(a.pm, b, min(next + kStep, last));
+      block_step<true>(w, kr, vr, qb, K4 + base, V4 + base, row0, row_last, tok0, t_end, r16, kg, a.scale_log2);
 #if SR_TIMELINE
       if (first) { SR_STAMP(a, 2); first = false; }
 #endif
       tok0 = next;
-      next += kWaves * kBlock;
+      next += kStep;
     }
-    block_step<false>(w, kr, vr, qb, K4, V4, tok0, next, t_end, last, r16, kg, a.scale_log2);
+    block_step<false>(w, kr, vr, qb, K4, V4, 0, 0, tok0, t_end, r16, kg, a.scale_log2);
   }
 
   // ---- merge the 4 wavefronts through LDS, write one partial per head
@@ -490,6 +539,7 @@ __device__ __forceinline__ void attend_range(const PartialArgs& a, int b, int g,
 }
 
 // Fixed schedule.  grid = (num_splits, B*H_kv), block = 256.
+template <bool kPaged>
 __global__ __launch_bounds__(kThreads, 2) void sr_partial_fixed_kernel(PartialArgs a) {
   const int s = blockIdx.x;
   const int bg = blockIdx.y;
@@ -498,7 +548,7 @@ __global__ __launch_bounds__(kThreads, 2) void sr_partial_fixed_kernel(PartialAr
   const int L = clamp_len(a.seq_lens[b], a.Lmax);
   const int t_begin = s * a.chunk;
   if (t_begin >= L) return;                     // chunk lies beyond this sequence
-  attend_range(a, b, g, L, t_begin, min(t_begin + a.chunk, L), s);
+  attend_range<kPaged>(a, b, g, L, t_begin, min(t_begin + a.chunk, L), s);
 }
 
 // Balanced schedule.  grid = kBalancedGrid, block = 256.  Unit = one 64-token block of an Active
@@ -509,7 +559,7 @@ __global__ __launch_bounds__(kThreads, 2) void sr_partial_fixed_kernel(PartialAr
 // and anchor rows are a few tens of KB, served by L2), as the paper's kernel does inline, so no
 // separate probe launch precedes it; workgroup 0 writes skip mask and group scores.  Otherwise
 // the mask written by sr_probe_kernel is read.
-template <bool kFused>
+template <bool kFused, bool kPaged>
 __global__ __launch_bounds__(kThreads, 2) void sr_partial_balanced_kernel(PartialArgs a) {
   __shared__ int start[kMaxSchedGroups + 1];
   __shared__ int lens[kMaxSchedGroups];
@@ -533,7 +583,7 @@ __global__ __launch_bounds__(kThreads, 2) void sr_partial_balanced_kernel(Partia
         hd = hd < NH ? hd : NH - 1;
         const int i = hd / G;
         const uint4* qrow = q4 + (size_t)hd * (kD / 8);
-        const uint4* krow = anchor_row(a.k, a.k0, i, a.Lmax);
+        const uint4* krow = anchor_row(a.k, a.k0, i, a.Lmax, a.Hkv, a.pm);
 #pragma unroll
         for (int j = 0; j < 4; ++j) { qw[u][j] = qrow[lane4 + 4 * j]; kw[u][j] = krow[lane4 + 4 * j]; }
         kn[u] = a.k0_norm ? a.k0_norm[i] : -1.f;
@@ -600,7 +650,7 @@ __global__ __launch_bounds__(kThreads, 2) void sr_partial_balanced_kernel(Partia
     const int b = i / a.Hkv, g = i - b * a.Hkv;
     const int L = lens[i];
     const int blk_lo = max(u_lo, s0) - s0, blk_hi = min(u_hi, s1) - s0;
-    attend_range(a, b, g, L, blk_lo * kBlock, min(blk_hi * kBlock, L), p - s0 / c);
+    attend_range<kPaged>(a, b, g, L, blk_lo * kBlock, min(blk_hi * kBlock, L), p - s0 / c);
     __syncthreads();                            // LDS of attend_range is reused by the next segment
   }
   SR_STAMP(a, 5);
@@ -619,7 +669,7 @@ struct CombineArgs {
   int Hq, Hkv, G, Lmax, chunk, slots;
   // diagnostics (optional): log-sum-exp of the scaled scores and softmax mass on token 0 per head
   const uint32_t* q;      // bf16 pairs
-  const void* k;
+  const void* k;          // contiguous key cache (diagnostics are not offered for paged caches)
   float* lse_out;
   float* alpha0_out;
   float scale_log2;
@@ -700,7 +750,7 @@ __global__ __launch_bounds__(kCombineThreads) void sr_combine_kernel(CombineArgs
       const float lse2 = M + __builtin_amdgcn_logf(l);                  // log2 domain (v_log_f32 is log2)
       if (a.alpha0_out) {                                               // alpha_0 = exp(z_0 - lse), Section 4.2
         const uint32_t qw = a.q[(size_t)bh * (kD / 2) + lane];
-        const uint32_t kw = reinterpret_cast<const uint32_t*>(anchor_row(a.k, nullptr, bg, a.Lmax))[lane];   // token 0 of the cache itself
+        const uint32_t kw = reinterpret_cast<const uint32_t*>(a.k)[(size_t)bg * a.Lmax * (kD / 2) + lane];   // token 0 of the cache itself
         float d = bf16_lo(qw) * bf16_lo(kw) + bf16_hi(qw) * bf16_hi(kw);
 #pragma unroll
         for (int o = 32; o >= 1; o >>= 1) d += __shfl_xor(d, o, 64);
@@ -815,8 +865,9 @@ RouteRule make_rule(const sr_route_params* p) {
 }
 
 int launch_probe(const void* q, const void* k, const int32_t* seq_lens, const sr_route_params* p,
-                 const Layout& lay, float* score, uint8_t* mask, hipStream_t st) {
+                 const Layout& lay, float* score, uint8_t* mask, hipStream_t st, const PageMap& pm) {
   ProbeArgs a;
+  a.pm = pm;
   a.q = static_cast<const uint4*>(q);
   a.k = k;
   a.k0 = p->k0;
@@ -832,7 +883,7 @@ int launch_probe(const void* q, const void* k, const int32_t* seq_lens, const sr
 
 int decode_impl(const void* q, const void* k, const void* v, const int32_t* seq_lens,
                 const sr_route_params* p, void* out, uint8_t* mask, float* stage_us,
-                float* lse_out = nullptr, float* alpha0_out = nullptr) {
+                float* lse_out = nullptr, float* alpha0_out = nullptr, const PageMap* pages = nullptr) {
   if (!q || !k || !v || !seq_lens || !p || !out || !mask) return SR_ERR_NULL;
   Layout lay;
   int rc = make_layout(p, &lay);
@@ -849,6 +900,9 @@ int decode_impl(const void* q, const void* k, const void* v, const int32_t* seq_
   float* score = reinterpret_cast<float*>(ws + lay.off_score);
   int32_t* sched = reinterpret_cast<int32_t*>(ws + lay.off_sched);
   const bool balanced = lay.plan.schedule == 1;
+  PageMap pm = {nullptr, 0, 0, 0};
+  if (pages) pm = *pages;
+  const bool paged = pm.table != nullptr;
   const bool fused = balanced && (int64_t)p->batch * p->n_q_heads <= kMaxFusedHeads;
 
   hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
@@ -861,7 +915,7 @@ int decode_impl(const void* q, const void* k, const void* v, const int32_t* seq_
   }
   auto mark = [&](int i) { return !stage_us || hipEventRecord(ev[i], st) == hipSuccess; };
   bool ok = mark(0);
-  if (ok && !fused) ok = launch_probe(q, k, seq_lens, p, lay, score, mask, st) == SR_OK;
+  if (ok && !fused) ok = launch_probe(q, k, seq_lens, p, lay, score, mask, st, pm) == SR_OK;
   if (ok) ok = mark(1);
   if (ok) {
     PartialArgs a;
@@ -878,12 +932,14 @@ int decode_impl(const void* q, const void* k, const void* v, const int32_t* seq_
     a.chunk = lay.plan.chunk_tokens; a.slots = lay.plan.slots_per_head;
     const float scale = p->sm_scale > 0.f ? p->sm_scale : 0.08838834764831845f;   // 1/sqrt(128)
     a.scale_log2 = scale * 1.4426950408889634f;
-    if (fused)
-      hipLaunchKernelGGL(sr_partial_balanced_kernel<true>, dim3(kBalancedGrid), dim3(64 * kWaves), 0, st, a);
-    else if (balanced)
-      hipLaunchKernelGGL(sr_partial_balanced_kernel<false>, dim3(kBalancedGrid), dim3(64 * kWaves), 0, st, a);
-    else
-      hipLaunchKernelGGL(sr_partial_fixed_kernel, dim3(lay.plan.num_splits, a.NG), dim3(64 * kWaves), 0, st, a);
+    a.pm = pm;
+    const dim3 blk(kThreads), fixed_grid(lay.plan.num_splits, a.NG);
+    if (fused && paged)       hipLaunchKernelGGL((sr_partial_balanced_kernel<true, true>), dim3(kBalancedGrid), blk, 0, st, a);
+    else if (fused)           hipLaunchKernelGGL((sr_partial_balanced_kernel<true, false>), dim3(kBalancedGrid), blk, 0, st, a);
+    else if (balanced && paged) hipLaunchKernelGGL((sr_partial_balanced_kernel<false, true>), dim3(kBalancedGrid), blk, 0, st, a);
+    else if (balanced)        hipLaunchKernelGGL((sr_partial_balanced_kernel<false, false>), dim3(kBalancedGrid), blk, 0, st, a);
+    else if (paged)           hipLaunchKernelGGL(sr_partial_fixed_kernel<true>, fixed_grid, blk, 0, st, a);
+    else                      hipLaunchKernelGGL(sr_partial_fixed_kernel<false>, fixed_grid, blk, 0, st, a);
     ok = hipGetLastError() == hipSuccess;
   }
   const float scale_log2 = (p->sm_scale > 0.f ? p->sm_scale : 0.08838834764831845f) * 1.4426950408889634f;
@@ -958,8 +1014,9 @@ int sinkrouter_probe(const void* q, const void* k_cache, const int32_t* seq_lens
   if (misaligned(q, 16) || misaligned(k_cache, 16) || misaligned(seq_lens, 4) || misaligned(group_score_out, 4) ||
       misaligned(params->k0, 16) || misaligned(params->k0_norm, 4))
     return SR_ERR_ALIGN;
+  const PageMap none = {nullptr, 0, 0, 0};
   return launch_probe(q, k_cache, seq_lens, params, lay, group_score_out, skip_mask_out,
-                      static_cast<hipStream_t>(params->stream));
+                      static_cast<hipStream_t>(params->stream), none);
 }
 
 int sinkrouter_decode_diag(const void* q, const void* k_cache, const void* v_cache, const int32_t* seq_lens,
@@ -969,6 +1026,24 @@ int sinkrouter_decode_diag(const void* q, const void* k_cache, const void* v_cac
   return decode_impl(q, k_cache, v_cache, seq_lens, params, out, skip_mask_out, nullptr, lse_out, alpha0_out);
 }
 
+int sinkrouter_decode_paged(const void* q, const void* k_pages, const void* v_pages, const int32_t* block_table,
+                            const int32_t* seq_lens, const sr_route_params* params, const sr_paged_layout* layout,
+                            void* out, uint8_t* skip_mask_out) {
+  if (!block_table || !layout || !params) return SR_ERR_NULL;
+  if (layout->struct_size != sizeof(sr_paged_layout)) return SR_ERR_UNSUPPORTED;
+  const int pt = layout->page_tokens;
+  if (pt < kBlock || (pt & (pt - 1)) != 0) return SR_ERR_UNSUPPORTED;       // power of two, >= one block
+  if (layout->n_pages < 1 || layout->pages_per_seq < 1) return SR_ERR_SHAPE;
+  if (params->max_seq_len < 1 || (int64_t)layout->pages_per_seq * pt < params->max_seq_len) return SR_ERR_SHAPE;
+  if (misaligned(block_table, 4)) return SR_ERR_ALIGN;
+  PageMap pm;
+  pm.table = block_table;
+  pm.page_shift = __builtin_ctz((unsigned)pt);
+  pm.pages_per_seq = layout->pages_per_seq;
+  pm.n_pages = layout->n_pages;
+  return decode_impl(q, k_pages, v_pages, seq_lens, params, out, skip_mask_out, nullptr, nullptr, nullptr, &pm);
+}
+
 int sinkrouter_extract_anchor(const void* k_cache, const sr_route_params* params, void* k0_out, float* k0_norm_out) {
   if (!k_cache || !params || (!k0_out && !k0_norm_out)) return SR_ERR_NULL;
   Layout lay;
@@ -976,8 +1051,9 @@ int sinkrouter_extract_anchor(const void* k_cache, const sr_route_params* params
   if (rc != SR_OK) return rc;
   if (misaligned(k_cache, 16) || misaligned(k0_out, 16) || misaligned(k0_norm_out, 4)) return SR_ERR_ALIGN;
   const int NG = params->batch * params->n_kv_heads;
+  const PageMap none = {nullptr, 0, 0, 0};
   hipLaunchKernelGGL(sr_anchor_kernel, dim3((NG + 15) / 16), dim3(64), 0, static_cast<hipStream_t>(params->stream),
-                     k_cache, static_cast<uint4*>(k0_out), k0_norm_out, NG, params->max_seq_len);
+                     k_cache, static_cast<uint4*>(k0_out), k0_norm_out, NG, params->max_seq_len, params->n_kv_heads, none);
   return hipGetLastError() == hipSuccess ? SR_OK : SR_ERR_HIP;
 }
 

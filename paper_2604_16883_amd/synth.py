@@ -290,3 +290,27 @@ def random_small(seed: int, B: int, Hq: int, Hkv: int, D: int, Lmax: int,
         k[b, :, int(sl[b]):] = BF16_NAN
         v[b, :, int(sl[b]):] = BF16_NAN
     return q, k, v, sl
+
+
+def to_pages(cache: np.ndarray, seq_lens, page_tokens: int, seed: int, spare_pages: int = 3):
+    """Scatter a contiguous cache [B,Hkv,Lmax,D] into a page pool in a seeded random page order.
+
+    Returns (pages [n_pages,Hkv,page_tokens,D], block_table [B,pages_per_seq] int32).  Unused pool pages and the
+    unused tail of each sequence's last page hold NaN bit patterns; table entries beyond a sequence's last page are -1.
+    """
+    B, Hkv, Lmax, D = cache.shape
+    sl = np.asarray(seq_lens, np.int64)
+    pps = (Lmax + page_tokens - 1) // page_tokens
+    need = [(int(L) + page_tokens - 1) // page_tokens for L in sl]
+    n_pages = sum(need) + spare_pages
+    order = _rng(seed, 77).permutation(n_pages)
+    pages = np.full((n_pages, Hkv, page_tokens, D), BF16_NAN, np.uint16)
+    table = np.full((B, pps), -1, np.int32)
+    nxt = 0
+    for b in range(B):
+        for j in range(need[b]):
+            pg = int(order[nxt]); nxt += 1
+            table[b, j] = pg
+            t0, t1 = j * page_tokens, min((j + 1) * page_tokens, int(sl[b]))
+            pages[pg, :, :t1 - t0] = cache[b, :, t0:t1]
+    return pages, table

@@ -370,6 +370,31 @@ def check_separate_anchor(lib=None):
     np.testing.assert_allclose(o2, alt.out, rtol=1e-12, atol=1e-13)
 
 
+def check_paged_gather(lib=None):
+    """Gathering pages == numpy fancy indexing; a paged decode == the decode on the contiguous cache it
+    came from, whatever the physical page order."""
+    B, Hq, Hkv, D, L, pt = 3, 4, 2, 8, 23, 4
+    q, k, v, sl = synth.random_small(900, B, Hq, Hkv, D, L, [L, 9, 4])
+    ref = oracle.decode(q, k, v, sl, tau_coef=(0, 0, 0, 0.05), want_dense=True, libpath=lib)
+    for seed in (1, 2):
+        kp, tab = synth.to_pages(k, sl, pt, seed)
+        vp, tab2 = synth.to_pages(v, sl, pt, seed)
+        assert np.array_equal(tab, tab2)
+        got = oracle.gather_pages(kp, tab, sl, L, libpath=lib)
+        for b in range(B):
+            Lb = int(sl[b])
+            t = np.arange(Lb)
+            expect = kp[tab[b, t // pt], :, t % pt].transpose(1, 0, 2)       # [Hkv, Lb, D]
+            assert np.array_equal(got[b, :, :Lb], expect)
+            assert np.array_equal(got[b, :, :Lb], k[b, :, :Lb])
+            assert np.all(got[b, :, Lb:] == 0)
+        r = oracle.decode_paged(q, kp, vp, tab, sl, L, tau_coef=(0, 0, 0, 0.05), want_dense=True, libpath=lib)
+        np.testing.assert_array_equal(r.out, ref.out)
+        np.testing.assert_array_equal(r.mask, ref.mask)
+        np.testing.assert_array_equal(r.group_score, ref.group_score)
+    assert ref.mask.any() and not ref.mask.all()
+
+
 ALL_PINS = [check_golden, check_brute_force_dense, check_routed_vs_library,
             check_splitk_equals_single_pass, check_closed_forms, check_cosine_properties,
-            check_decision_properties, check_skip_error_bound, check_symmetries, check_separate_anchor]
+            check_decision_properties, check_skip_error_bound, check_symmetries, check_separate_anchor, check_paged_gather]

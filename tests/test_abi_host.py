@@ -146,6 +146,20 @@ def test_alignment_and_workspace_errors():
     assert lib.sinkrouter_hbm_read_probe((1 << 16) + 4, 1024, 1 << 17, None) == B.SR_ERR_ALIGN
 
 
+def test_paged_argument_errors():
+    p = B.make_route_params(1, 32, 8, 4096, workspace=0x70000, workspace_bytes=1 << 30)
+    args = (0x10000, 0x20000, 0x30000, 0x80000, 0x40000)
+    for lay, code in ((B.make_paged_layout(48, 100, 10), B.SR_ERR_UNSUPPORTED),
+                      (B.make_paged_layout(32, 200, 10), B.SR_ERR_UNSUPPORTED),
+                      (B.make_paged_layout(64, 10, 10), B.SR_ERR_SHAPE),
+                      (B.make_paged_layout(64, 64, 0), B.SR_ERR_SHAPE)):
+        assert B.sinkrouter_decode_paged(*args, p, lay, 0x50000, 0x60000, check=False) == code
+    lay = B.make_paged_layout(64, 64, 10)
+    assert B.sinkrouter_decode_paged(0x10000, 0x20000, 0x30000, None, 0x40000, p, lay, 0x50000, 0x60000, check=False) == B.SR_ERR_NULL
+    lay.struct_size += 4
+    assert B.sinkrouter_decode_paged(*args, p, lay, 0x50000, 0x60000, check=False) == B.SR_ERR_UNSUPPORTED
+
+
 def test_compute_call_without_gpu_fails_loudly():
     import torch
     if torch.cuda.is_available():

@@ -42,6 +42,10 @@ MUTANTS = [
      ": k_cache + ((size_t)b * Hkv + g) * (size_t)c->max_seq_len * D + (size_t)(L > 0 ? L - 1 : 0) * D;"),
     ("separate_anchor_ignored", "const uint16_t* k0 = k0_rows ? k0_rows + ((size_t)b * Hkv + g) * D",
      "const uint16_t* k0 = (0 && k0_rows) ? k0_rows + ((size_t)b * Hkv + g) * D"),
+    ("page_row_ignores_offset", "* page_tokens + (t % page_tokens)) * D;", "* page_tokens) * D;"),
+    ("page_group_stride_wrong", "const uint16_t* src = pages + (((size_t)page * Hkv + g) * page_tokens",
+     "const uint16_t* src = pages + (((size_t)page + (size_t)g * n_pages) * page_tokens"),
+    ("page_table_row_stride_wrong", "int32_t page = table[(size_t)b * pages_per_seq + j];", "int32_t page = table[(size_t)b + j];"),
     ("separate_anchor_wrong_group", "k0_rows + ((size_t)b * Hkv + g) * D", "k0_rows + ((size_t)b * Hkv) * D"),
 ]
 
