@@ -62,6 +62,23 @@ def test_group_sizes(Hq, Hkv):
     _check(sb, label="Hq%d/Hkv%d" % (Hq, Hkv))
 
 
+def test_large_batches_take_the_unfused_and_fixed_paths():
+    # more than 512 query heads in the batch: separate probe kernel + balanced schedule
+    w = synth.Workload("wide", 20, 32, 8, 300, 0.6, base_seed=91)
+    sb = synth.generate(w, seq_lens=[300 - 7 * b for b in range(20)])
+    reps = _check(sb, label="B20 (unfused probe)")
+    assert 0 < reps[0]["skip_ratio"] < 1
+    # more than 2048 (sequence, group) pairs: falls back to fixed chunks
+    w = synth.Workload("many", 300, 16, 8, 130, 0.6, base_seed=92)
+    sb = synth.generate(w, seq_lens=[130 - (b % 67) for b in range(300)])
+    res = gu.run_hip(sb.q, sb.k, sb.v, sb.seq_lens)
+    assert res["plan"].schedule == 0
+    ref = oracle.decode(sb.q, sb.k, sb.v, sb.seq_lens, want_dense=True)
+    rep = gu.compare(res, ref, 2, "B300 (fixed fallback)")
+    print("B300", rep, flush=True)
+    assert 0 < rep["skip_ratio"] < 1
+
+
 def test_edge_lengths():
     # lengths 0 and 1, exactly one block, one block + 1, all with a poisoned tail beyond seq_len
     w = synth.Workload("edge", 6, 8, 2, 300, 0.5, base_seed=77)
