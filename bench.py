@@ -220,8 +220,8 @@ def main():
     ap.add_argument("-v", "--verbose", action="store_true")
     a = ap.parse_args()
     if a.gpus != 1:
-        print("bench.py: this build runs on one GPU; --gpus %d is not supported (the path shards by KV "
-              "group across GPUs with no exchange, see DESIGN.md)" % a.gpus, file=sys.stderr)
+        print("bench.py: this build runs on one GPU; --gpus %d is not supported (KV groups are independent, so "
+              "the path would shard by group across GPUs with no exchange; only N=1 is built)" % a.gpus, file=sys.stderr)
         sys.exit(2)
     import torch
     if not torch.cuda.is_available():

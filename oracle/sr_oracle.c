@@ -20,7 +20,7 @@
  *     partial per chunk, merged afterwards                (Section 4.3, Split-K paragraph;
  *     the paper does not print the merge, the standard log-sum-exp merge is used)
  *
- * Readings where the paper is silent (each also listed in the design notes):
+ * Readings where the paper is silent:
  *   softmax scale defaults to 1/sqrt(D); seq_lens[b] counts valid cache rows
  *   including the current token; token 0 is row 0 of the cache of that
  *   (sequence, KV group); a zero norm makes the cosine 0; a NaN score keeps
