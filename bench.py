@@ -251,8 +251,8 @@ def main():
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": round(routed["us_per_step"] / 1e3, 5),
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16 in, fp32 accumulate", "data": "synthetic (seeded, sink-planted KV cache resident in HBM)",
-        "config": {"workload": "%s: %s" % (a.workload, main_res["description"]), "kv_block": 64,
+        "dtype": "bf16", "data": "synthetic (seeded, sink-planted KV cache resident in HBM)",
+        "config": {"workload": "%s: %s" % (a.workload, main_res["description"]), "kv_block": 64, "accumulate": "fp32",
                    "threshold": 0.55, "skip_ratio": routed["skip_ratio"],
                    "schedule": routed["schedule"], "partial_grid": routed["partial_grid"]},
         "roofline": {"bound": "hbm", "kernel": "sr_partial_balanced_kernel (routing probe fused)", "achieved": achieved, "peak": HBM_PEAK_GBS,

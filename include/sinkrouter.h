@@ -119,7 +119,10 @@ size_t sinkrouter_workspace_bytes(const sr_route_params* params /*host*/);
  *                 (fp32 accumulation, rounded to nearest even), exact zeros for heads of
  *                 Sink Groups and for sequences of length 0
  *   skip_mask_out device uint8 [B,H_kv]: 1 = Sink Group (skipped), 0 = Active Group
- * Three kernels are enqueued on params->stream: routing probe, Split-K partial, merge.
+ * Enqueued on params->stream: the Split-K partial kernel, which evaluates the routing rule itself
+ * (a separate routing-probe kernel precedes it for batches of more than 512 query heads or with
+ * fixed chunks), then the merge kernel.  Nothing is allocated, no memset is recorded and nothing
+ * synchronises, so the call can be captured into a HIP graph.
  */
 int sinkrouter_decode(const void* q, const void* k_cache, const void* v_cache,
                       const int32_t* seq_lens, const sr_route_params* params,
@@ -137,9 +140,9 @@ int sinkrouter_probe(const void* q, const void* k_cache, const int32_t* seq_lens
 
 /*
  * sinkrouter_decode with per-kernel timing, for benchmarks: HIP events are recorded on
- * params->stream around each of the three kernels and the call SYNCHRONISES the stream
- * before returning.  stage_us (host, 4 floats): probe, Split-K partial, merge, total, in
- * microseconds.
+ * params->stream around each kernel and the call SYNCHRONISES the stream before returning.
+ * stage_us (host, 4 floats), in microseconds: separate probe kernel (the gap between two events
+ * when the probe is fused into the partial kernel), Split-K partial, merge, total.
  */
 int sinkrouter_decode_profiled(const void* q, const void* k_cache, const void* v_cache,
                                const int32_t* seq_lens, const sr_route_params* params,

@@ -1,9 +1,11 @@
 // SinkRouter decode attention for MI355X (gfx950, CDNA4): kernels and the C ABI.
 //
-// Three kernels per decode step, all on the caller's stream:
-//   sr_probe_kernel    routing signal of Section 4.2 (Eq. 8-10): one workgroup per
-//                      (sequence, KV group), one wavefront per query head; reads the
-//                      group's query heads and row 0 of K only.
+// Kernels of one decode step, all on the caller's stream:
+//   sr_probe_kernel    routing signal of Section 4.2 (Eq. 8-10): one wavefront per
+//                      (sequence, KV group), four lanes per query head; reads the group's query
+//                      heads and token 0 of K only.  Normally fused into the balanced partial
+//                      kernel (every workgroup evaluates the rule for all groups itself); launched
+//                      on its own for large batches, fixed chunks and sinkrouter_probe.
 //   sr_partial_*       Split-K partial attention of Section 4.3 for Active Groups only.
 //                      Each wavefront streams 64-token K/V blocks straight from HBM into
 //                      registers with 128-bit loads and feeds them to the matrix cores: all
@@ -13,9 +15,10 @@
 //                      softmax per block.  The 4 wavefronts of a workgroup interleave blocks
 //                      and merge their results through LDS into one partial (m, l, o) per
 //                      (head, workgroup).  Two schedules:
-//        balanced  (default) one workgroup per compute unit; every workgroup first scans the
-//                  skip mask, so the 64-token blocks of the Active Groups only are dealt out
-//                  in equal contiguous shares.  Sink Groups cost nothing and the chip stays
+//        balanced  (default) one workgroup per compute unit; every workgroup first obtains the
+//                  skip decisions of all groups (fused probe, or the mask of sr_probe_kernel), so
+//                  the 64-token blocks of the Active Groups only are dealt out in equal contiguous
+//                  shares.  Sink Groups cost nothing and the chip stays
 //                  full whatever the skip pattern is.
 //        fixed     the paper's literal Split-K: [0, L) cut into num_splits chunks, one
 //                  workgroup per (chunk, sequence, KV group); workgroups of Sink Groups
@@ -597,6 +600,7 @@ __global__ __launch_bounds__(kThreads, 2) void sr_partial_balanced_kernel(Partia
     }
   }
   __syncthreads();
+  SR_STAMP(a, 6);
   int carry = 0;
   for (int base = 0; base < NG; base += kThreads) {
     const int i = base + tid;
