@@ -571,6 +571,8 @@ __global__ __launch_bounds__(kThreads, 2) void sr_partial_balanced_kernel(Partia
   __shared__ int first_group;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int NG = a.NG, G = a.G;
+  // share index = workgroup index: the stream has no reuse, so which XCD works on which share is
+  // immaterial (giving each XCD one contiguous eighth of the blocks measured the same)
   const int p = blockIdx.x, P = gridDim.x;
   SR_STAMP(a, 0);
   for (int i = tid; i < NG; i += kThreads) lens[i] = clamp_len(a.seq_lens[i / a.Hkv], a.Lmax);
