@@ -177,3 +177,33 @@ def test_missing_library_raises(tmp_path, monkeypatch):
     monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "nope.so"))
     with pytest.raises(FileNotFoundError):
         B.load()
+
+
+def test_header_is_plain_c(tmp_path):
+    """The boundary header must compile as strict C99 and as C++ with no other include."""
+    import subprocess
+    src = tmp_path / "use.c"
+    src.write_text('#include "sinkrouter.h"\n'
+                   'int f(void) { sr_route_params p; sr_plan pl; sr_paged_layout lay; p.struct_size = sizeof p; lay.struct_size = sizeof lay;\n'
+                   '  (void)lay; return sinkrouter_plan(&p, &pl) + (int)sizeof(sr_status) + SINKROUTER_ABI_VERSION; }\n')
+    inc = os.path.join(ROOT, "include")
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-I", inc, str(src)], check=True)
+    cpp = tmp_path / "use.cpp"
+    cpp.write_text(src.read_text())
+    subprocess.run(["g++", "-std=c++11", "-pedantic", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-I", inc, str(cpp)], check=True)
+
+
+def test_struct_sizes_match_the_c_compiler(tmp_path):
+    """ctypes mirrors and the C compiler agree on sizes and field offsets."""
+    import subprocess
+    src = tmp_path / "sizes.c"
+    src.write_text('#include <stdio.h>\n#include <stddef.h>\n#include "sinkrouter.h"\n'
+                   'int main(void) { printf("%zu %zu %zu %zu %zu %zu %zu\\n", sizeof(sr_route_params), offsetof(sr_route_params, tau_coef),\n'
+                   '  offsetof(sr_route_params, k0_norm), offsetof(sr_route_params, workspace), offsetof(sr_route_params, stream),\n'
+                   '  sizeof(sr_plan), sizeof(sr_paged_layout)); return 0; }\n')
+    exe = tmp_path / "sizes"
+    subprocess.run(["gcc", "-std=c99", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)], check=True)
+    got = [int(x) for x in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
+    P = B.RouteParams
+    assert got == [ctypes.sizeof(P), P.tau_coef.offset, P.k0_norm.offset, P.workspace.offset, P.stream.offset,
+                   ctypes.sizeof(B.Plan), ctypes.sizeof(B.PagedLayout)]
