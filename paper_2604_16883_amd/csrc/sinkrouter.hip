@@ -36,17 +36,6 @@
 
 #include "sinkrouter.h"
 
-#ifndef SR_FINE_PREFETCH
-#define SR_FINE_PREFETCH 1
-#endif
-#ifndef SR_TIMELINE
-#define SR_TIMELINE 0     // 1: debug build, every workgroup leaves 8 wall-clock stamps behind the workspace
-#endif
-#if SR_TIMELINE
-#define SR_STAMP(a, i) do { if (threadIdx.x == 0) (a).timeline[blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
-#else
-#define SR_STAMP(a, i) do { } while (0)
-#endif
 #ifndef SR_P_SPLIT
 #define SR_P_SPLIT 1      // softmax weights enter the P.V MFMA as bf16 hi + bf16 lo (1) or bf16 only (0)
 #endif
@@ -272,9 +261,6 @@ struct PartialArgs {
   int slots;        // partial records per head
   float scale_log2; // softmax scale * log2(e)
   PageMap pm;
-#if SR_TIMELINE
-  long long* timeline;
-#endif
 };
 
 // Loads of one 64-token block whose first row is row0 of the slab at Kbase / Vbase (a contiguous
@@ -329,20 +315,10 @@ __device__ __forceinline__ void block_step(WaveState& w, uint4 (&kr)[4][4], uint
 #pragma unroll
     for (int j = 0; j < 4; ++j)
       sc[T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kr[T][j]), qb[j], sc[T], 0, 0, 0);
-#if SR_FINE_PREFETCH
     __builtin_amdgcn_sched_barrier(0);
     if (kPrefetch) load_k_tile(kr[T], Kn, row0_n, T, r16, kg, row_last_n);
     __builtin_amdgcn_sched_barrier(0);
-#endif
   }
-#if !SR_FINE_PREFETCH
-  __builtin_amdgcn_sched_barrier(0);
-  if (kPrefetch) {
-#pragma unroll
-    for (int T = 0; T < 4; ++T) load_k_tile(kr[T], Kn, row0_n, T, r16, kg, row_last_n);
-  }
-  __builtin_amdgcn_sched_barrier(0);
-#endif
   // ---- online softmax over the block
   float bm = -INFINITY;
 #pragma unroll
@@ -414,20 +390,10 @@ __device__ __forceinline__ void block_step(WaveState& w, uint4 (&kr)[4][4], uint
 #endif
       }
     }
-#if SR_FINE_PREFETCH
     __builtin_amdgcn_sched_barrier(0);
     if (kPrefetch) { load_v_tile(vr[T], Vn, row0_n, T, r16, kg, row_last_n); load_v_tile(vr[T + 1], Vn, row0_n, T + 1, r16, kg, row_last_n); }
     __builtin_amdgcn_sched_barrier(0);
-#endif
   }
-#if !SR_FINE_PREFETCH
-  __builtin_amdgcn_sched_barrier(0);
-  if (kPrefetch) {
-#pragma unroll
-    for (int T = 0; T < 4; ++T) load_v_tile(vr[T], Vn, row0_n, T, r16, kg, row_last_n);
-  }
-  __builtin_amdgcn_sched_barrier(0);
-#endif
 }
 
 // Attention of the G heads of group (b, g) over tokens [t_begin, t_end) (t_begin a multiple of 64,
@@ -488,17 +454,11 @@ __device__ __forceinline__ void attend_range(const PartialArgs& a, int b, int g,
     int next = tok0 + kStep;
     // paged: the page of a block is looked up one iteration before the block is prefetched
     int page_n = (kPaged && next < t_end) ? page_of(a.pm, b, next) : 0;
-#if SR_TIMELINE
-    bool first = true;
-#endif
     while (next < t_end) {
       const size_t base = slab_base(page_n);
       const int row0 = slab_row(next), row_last = row0 + (last - next);
       if (kPaged) page_n = page_of(a.pm, b, min(next + kStep, last));
       block_step<true>(w, kr, vr, qb, K4 + base, V4 + base, row0, row_last, tok0, t_end, r16, kg, a.scale_log2);
-#if SR_TIMELINE
-      if (first) { SR_STAMP(a, 2); first = false; }
-#endif
       tok0 = next;
       next += kStep;
     }
@@ -506,7 +466,6 @@ __device__ __forceinline__ void attend_range(const PartialArgs& a, int b, int g,
   }
 
   // ---- merge the 4 wavefronts through LDS, write one partial per head
-  SR_STAMP(a, 3);
   float l_run = w.l_run;
   l_run += __shfl_xor(l_run, 16, 64);
   l_run += __shfl_xor(l_run, 32, 64);
@@ -538,7 +497,6 @@ __device__ __forceinline__ void attend_range(const PartialArgs& a, int b, int g,
     *reinterpret_cast<float4*>(a.part_o + rec * kD + 4 * c4) = o;
     if (c4 == 0) *reinterpret_cast<float2*>(a.part_ml + rec * 2) = make_float2(M, l);
   }
-  SR_STAMP(a, 4);
 }
 
 // Fixed schedule.  grid = (num_splits, B*H_kv), block = 256.
@@ -574,7 +532,6 @@ __global__ __launch_bounds__(kThreads, 2) void sr_partial_balanced_kernel(Partia
   // share index = workgroup index: the stream has no reuse, so which XCD works on which share is
   // immaterial (giving each XCD one contiguous eighth of the blocks measured the same)
   const int p = blockIdx.x, P = gridDim.x;
-  SR_STAMP(a, 0);
   for (int i = tid; i < NG; i += kThreads) lens[i] = clamp_len(a.seq_lens[i / a.Hkv], a.Lmax);
   if (kFused && a.rule.routing) {
     const int NH = NG * G, lane4 = tid & 3;
@@ -602,7 +559,6 @@ __global__ __launch_bounds__(kThreads, 2) void sr_partial_balanced_kernel(Partia
     }
   }
   __syncthreads();
-  SR_STAMP(a, 6);
   int carry = 0;
   for (int base = 0; base < NG; base += kThreads) {
     const int i = base + tid;
@@ -645,7 +601,6 @@ __global__ __launch_bounds__(kThreads, 2) void sr_partial_balanced_kernel(Partia
     for (int i = tid; i <= NG; i += kThreads) a.sched[2 + i] = start[i];
   }
   const int u_lo = p * c, u_hi = min(u_lo + c, U);
-  SR_STAMP(a, 1);
   if (u_lo >= u_hi) return;
   for (int i = tid; i < NG; i += kThreads)
     if (start[i] <= u_lo && u_lo < start[i + 1]) first_group = i;   // exactly one group holds u_lo
@@ -659,7 +614,6 @@ __global__ __launch_bounds__(kThreads, 2) void sr_partial_balanced_kernel(Partia
     attend_range<kPaged>(a, b, g, L, blk_lo * kBlock, min(blk_hi * kBlock, L), p - s0 / c);
     __syncthreads();                            // LDS of attend_range is reused by the next segment
   }
-  SR_STAMP(a, 5);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -854,9 +808,6 @@ int make_layout(const sr_route_params* p, Layout* lay) {
   lay->off_score = lay->off_ml + align_up(heads * S * 2 * sizeof(float), 256);
   lay->off_sched = lay->off_score + align_up((size_t)NG * sizeof(float), 256);
   pl.workspace_bytes = lay->off_sched + align_up((size_t)(NG + 3) * sizeof(int32_t), 256);
-#if SR_TIMELINE
-  pl.workspace_bytes += (size_t)kBalancedGrid * 8 * sizeof(long long);   // last bytes of the workspace
-#endif
   return SR_OK;
 }
 
@@ -930,9 +881,6 @@ int decode_impl(const void* q, const void* k, const void* v, const int32_t* seq_
     a.v = static_cast<const uint16_t*>(v);
     a.seq_lens = seq_lens; a.mask = mask; a.part_o = part_o; a.part_ml = part_ml; a.sched = sched;
     a.k0 = p->k0; a.k0_norm = p->k0_norm; a.group_score = score; a.rule = make_rule(p);
-#if SR_TIMELINE
-    a.timeline = reinterpret_cast<long long*>(ws + lay.plan.workspace_bytes - (size_t)kBalancedGrid * 8 * sizeof(long long));
-#endif
     a.Hq = p->n_q_heads; a.Hkv = p->n_kv_heads; a.G = lay.plan.group_size; a.Lmax = p->max_seq_len;
     a.NG = p->batch * p->n_kv_heads;
     a.chunk = lay.plan.chunk_tokens; a.slots = lay.plan.slots_per_head;
