@@ -68,6 +68,18 @@ def test_large_batches_take_the_unfused_and_fixed_paths():
     sb = synth.generate(w, seq_lens=[300 - 7 * b for b in range(20)])
     reps = _check(sb, label="B20 (unfused probe)")
     assert 0 < reps[0]["skip_ratio"] < 1
+    # exactly 512 query heads: the fused probe sweeps four times
+    w = synth.Workload("fused512", 16, 32, 8, 200, 0.6, base_seed=93)
+    sb = synth.generate(w, seq_lens=[200 - 11 * (b % 9) for b in range(16)])
+    reps = _check(sb, label="B16 (fused probe, 512 heads)")
+    assert 0 < reps[0]["skip_ratio"] < 1
+    # 2000 (sequence, group) pairs: the schedule scan runs eight rounds
+    w = synth.Workload("scan", 250, 16, 8, 100, 0.6, base_seed=94)
+    sb = synth.generate(w, seq_lens=[100 - (b % 41) for b in range(250)])
+    res = gu.run_hip(sb.q, sb.k, sb.v, sb.seq_lens)
+    assert res["plan"].schedule == 1
+    ref = oracle.decode(sb.q, sb.k, sb.v, sb.seq_lens, want_dense=True)
+    print("B250", gu.compare(res, ref, 2, "B250 (balanced, 2000 groups)"), flush=True)
     # more than 2048 (sequence, group) pairs: falls back to fixed chunks
     w = synth.Workload("many", 300, 16, 8, 130, 0.6, base_seed=92)
     sb = synth.generate(w, seq_lens=[130 - (b % 67) for b in range(300)])
