@@ -142,6 +142,7 @@ def run_workload(name, steps, warmup, copies, verbose, num_splits=0, page_tokens
         partial_us = float(np.mean(st[:, 1]))
         r = {
             "us_per_step": round(us, 2),
+            "step_us_events_p10_p50_p90": [round(float(x), 2) for x in np.percentile(st[:, 3], [10, 50, 90])],
             "probe_us": round(float(np.mean(st[:, 0])), 2),
             "partial_us": round(partial_us, 2),
             "partial_us_p10_p50_p90": [round(float(x), 2) for x in np.percentile(st[:, 1], [10, 50, 90])],
@@ -208,8 +209,8 @@ def cpu_baseline(sb, budget_s=20.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=60)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="c3", choices=["c0", "c1", "c2", "c3", "c4"])
     ap.add_argument("--also", default="c1", help="comma list of further workloads to report ('' for none)")
     ap.add_argument("--copies", type=int, default=3, help="distinct K/V copies rotated through")

@@ -726,15 +726,28 @@ __global__ __launch_bounds__(kCombineThreads) void sr_combine_kernel(CombineArgs
 // ------------------------------------------------------------------------------------------
 constexpr int kProbeGrid = 1024;
 
+// Streaming read at the pattern that measured fastest on MI355X: every wavefront reads whole 16 KB
+// pieces (16 non-temporal 128-bit loads per lane in flight), pieces dealt round-robin to the wavefronts.
 __global__ __launch_bounds__(256) void sr_read_probe_kernel(const uint4* __restrict__ p, size_t n16, uint32_t* sink) {
+  constexpr int U = 16;
+  const int lane = threadIdx.x & 63;
+  const size_t wave = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6), nw = (size_t)gridDim.x * 4;
+  const size_t piece = (size_t)U * 64;                     // 128-bit words per piece
   uint32_t x = 0;
-  const size_t stride = (size_t)gridDim.x * 256;
-  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-  for (; i + 3 * stride < n16; i += 4 * stride) {
-    const uint4 a = p[i], b = p[i + stride], c = p[i + 2 * stride], d = p[i + 3 * stride];
-    x ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+  size_t c = wave * piece;
+  for (; c + piece <= n16; c += nw * piece) {
+    uint4 a[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) a[u] = load_stream(p + c + (size_t)u * 64 + lane);
+#pragma unroll
+    for (int u = 0; u < U; ++u) x ^= a[u].x ^ a[u].y ^ a[u].z ^ a[u].w;
   }
-  for (; i < n16; i += stride) { const uint4 a = p[i]; x ^= a.x ^ a.y ^ a.z ^ a.w; }
+  // the tail that does not fill a whole round of pieces
+  const size_t done = n16 / piece * piece;
+  for (size_t i = done + (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) {
+    const uint4 a = p[i];
+    x ^= a.x ^ a.y ^ a.z ^ a.w;
+  }
 #pragma unroll
   for (int o = 32; o >= 1; o >>= 1) x ^= __shfl_xor(x, o, 64);
   __shared__ uint32_t red[4];
