@@ -82,7 +82,7 @@ def time_steps(fn, steps, warmup):
     return (time.perf_counter() - t0) / steps * 1e6
 
 
-def run_workload(name, steps, warmup, copies, verbose, num_splits=0, page_tokens=0):
+def run_workload(name, steps, warmup, copies, verbose, num_splits=0, page_tokens=0, use_graph=False):
     import torch
     from paper_2604_16883_amd import binding, synth
     w = synth.WORKLOADS[name]
@@ -128,6 +128,22 @@ def run_workload(name, steps, warmup, copies, verbose, num_splits=0, page_tokens
                 binding.sinkrouter_decode_paged(tq, ks[i], vs[i], table, tsl, p, layout, out, mask)
 
         us = time_steps(step, steps, warmup)
+        # the same steps replayed from one HIP graph (one decode call per K/V copy), which takes the
+        # host's launch path out of the picture
+        graph_us = None
+        if use_graph:
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                step()
+            torch.cuda.current_stream().wait_stream(side)
+            it[0] = 0
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                for _ in range(copies):
+                    step()
+            reps = max(1, steps // copies)
+            graph_us = time_steps(g.replay, reps, max(1, warmup // copies)) / copies
         # per-kernel durations from HIP events on the launch stream, same rotation
         st = np.zeros((steps, 4))
         for s in range(steps):
@@ -142,6 +158,7 @@ def run_workload(name, steps, warmup, copies, verbose, num_splits=0, page_tokens
         partial_us = float(np.mean(st[:, 1]))
         r = {
             "us_per_step": round(us, 2),
+            "us_per_step_graph_replay": None if graph_us is None else round(graph_us, 2),
             "step_us_events_p10_p50_p90": [round(float(x), 2) for x in np.percentile(st[:, 3], [10, 50, 90])],
             "probe_us": round(float(np.mean(st[:, 0])), 2),
             "partial_us": round(partial_us, 2),
@@ -216,6 +233,7 @@ def main():
     ap.add_argument("--copies", type=int, default=3, help="distinct K/V copies rotated through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--num-splits", type=int, default=0, help="0 = balanced schedule, >0 = fixed Split-K chunks")
+    ap.add_argument("--graph", action="store_true", help="also time the steps replayed from a captured HIP graph")
     ap.add_argument("--paged", type=int, default=0, metavar="PAGE_TOKENS",
                     help="run over a paged KV cache with this page size (power of two >= 64); 0 = contiguous")
     ap.add_argument("-v", "--verbose", action="store_true")
@@ -232,13 +250,13 @@ def main():
     binding.load()
 
     calib = hbm_calibration()
-    main_res, sb, _dev = run_workload(a.workload, a.steps, a.warmup, a.copies, a.verbose, a.num_splits, a.paged)
+    main_res, sb, _dev = run_workload(a.workload, a.steps, a.warmup, a.copies, a.verbose, a.num_splits, a.paged, a.graph)
     cpu = None if a.no_cpu_baseline else cpu_baseline(sb)
     del _dev
     torch.cuda.empty_cache()
     others = {}
     for name in [x for x in a.also.split(",") if x and x != a.workload]:
-        r, sb2, dev2 = run_workload(name, a.steps, a.warmup, max(a.copies, 4), a.verbose, a.num_splits, a.paged)
+        r, sb2, dev2 = run_workload(name, a.steps, a.warmup, max(a.copies, 4), a.verbose, a.num_splits, a.paged, a.graph)
         others[name] = r
         del sb2, dev2
         torch.cuda.empty_cache()
