@@ -235,6 +235,34 @@ def decode_splitk(q, k_cache, v_cache, seq_lens, bounds, *, tau_coef=(0.0, 0.0, 
     return out, mask, pm, pl
 
 
+def concentration(q, k_cache, v_cache, seq_lens, *, sm_scale: float = 0.0, libpath: Optional[str] = None):
+    """Per-head attention-concentration statistics (Section 3, Table 1): the softmax weight of
+    token 0, the largest and the mean weight of the other tokens, and the head update with token 0
+    left out.  Returns (alpha0, max_rest, mean_rest [B,Hq], out_rest [B,Hq,D]) in fp64."""
+    lib = _load(libpath)
+    q = np.ascontiguousarray(q)
+    B, Hq, D = q.shape
+    k_cache = np.ascontiguousarray(k_cache)
+    _, Hkv, Lmax, _ = k_cache.shape
+    q = _u16(q, (B, Hq, D))
+    k_cache = _u16(k_cache, (B, Hkv, Lmax, D))
+    v_cache = _u16(v_cache, (B, Hkv, Lmax, D))
+    sl = np.ascontiguousarray(np.asarray(seq_lens, dtype=np.int32))
+    assert sl.shape == (B,)
+    c = _cfg(B, Hq, Hkv, D, Lmax, False, False, sm_scale, (0.0, 0.0, 0.0, 0.0), 0.0)
+    a0 = np.empty((B, Hq), np.float64)
+    mx = np.empty((B, Hq), np.float64)
+    mean = np.empty((B, Hq), np.float64)
+    rest = np.empty((B, Hq, D), np.float64)
+    dp = ctypes.c_double
+    rc = lib.sr_oracle_concentration(
+        _ptr(q, ctypes.c_uint16), _ptr(k_cache, ctypes.c_uint16), _ptr(v_cache, ctypes.c_uint16),
+        _ptr(sl, ctypes.c_int32), ctypes.byref(c), _ptr(a0, dp), _ptr(mx, dp), _ptr(mean, dp), _ptr(rest, dp))
+    if rc != 0:
+        raise RuntimeError("sr_oracle_concentration failed: %d" % rc)
+    return a0, mx, mean, rest
+
+
 def gather_pages(pages, block_table, seq_lens, max_seq_len: int, libpath: Optional[str] = None) -> np.ndarray:
     """Paged pool [n_pages,Hkv,page_tokens,D] + block_table [B,pages_per_seq] -> contiguous cache
     [B,Hkv,max_seq_len,D] (rows beyond seq_lens[b] are zero)."""

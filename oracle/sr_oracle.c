@@ -16,6 +16,8 @@
  *   - Sink Groups output zero for all r heads             (Section 4.2, Eq. 11)
  *   - Active Groups: exact standard attention over the available cache
  *                                                         (Section 4.2, last paragraph)
+ *   - concentration statistics alpha_0, max and mean of the other weights
+ *                                                         (Section 3, Table 1)
  *   - Split-K over [chunk_start, chunk_end) with a max / sum / weighted-sum
  *     partial per chunk, merged afterwards                (Section 4.3, Split-K paragraph;
  *     the paper does not print the merge, the standard log-sum-exp merge is used)
@@ -308,6 +310,74 @@ int sr_oracle_decode_splitk(const uint16_t* q, const uint16_t* k_cache, const ui
     free(po);
     free(pm);
     free(pl);
+  }
+  return failed ? -3 : 0;
+}
+
+/*
+ * Attention-concentration statistics per head, the quantities of Table 1 (Section 3):
+ * with alpha = softmax of the scaled scores over the whole cache (Eq. 1),
+ *   alpha0    [B,H_q]  alpha_0, the weight of token 0
+ *   max_rest  [B,H_q]  max over t >= 1 of alpha_t
+ *   mean_rest [B,H_q]  (sum over t >= 1 of alpha_t) / (L - 1)
+ *   out_rest  [B,H_q,D] optional: the head update with token 0 left out and the remaining
+ *             weights renormalised, sum_{t>=1} alpha_t v_t / sum_{t>=1} alpha_t
+ * Routing plays no part.  L = 1: max_rest = mean_rest = 0 and out_rest = 0; L = 0: NaN, out_rest = 0.
+ */
+int sr_oracle_concentration(const uint16_t* q, const uint16_t* k_cache, const uint16_t* v_cache,
+                            const int32_t* seq_lens, const sr_oracle_cfg* c,
+                            double* alpha0, double* max_rest, double* mean_rest, double* out_rest) {
+  if (!q || !k_cache || !seq_lens || !c || !alpha0 || !max_rest || !mean_rest) return -1;
+  if (out_rest && !v_cache) return -1;
+  const int B = c->batch, Hq = c->n_q_heads, Hkv = c->n_kv_heads, D = c->head_dim;
+  if (B < 1 || Hq < 1 || Hkv < 1 || D < 1 || Hq % Hkv != 0 || c->max_seq_len < 1) return -2;
+  const int r = Hq / Hkv;
+  const double scale = scale_of(c);
+  const int32_t Lmax = c->max_seq_len;
+  int failed = 0;
+#pragma omp parallel
+  {
+    double* w = (double*)malloc(sizeof(double) * (size_t)Lmax);
+    if (!w) {
+#pragma omp atomic write
+      failed = 1;
+    }
+#pragma omp for schedule(dynamic, 1)
+    for (int bh = 0; bh < B * Hq; ++bh) {
+      if (!w) continue;
+      const int b = bh / Hq, h = bh % Hq, g = h / r;
+      const int32_t L = clamp_len(seq_lens[b], Lmax);
+      double* orow = out_rest ? out_rest + (size_t)bh * D : NULL;
+      if (orow) for (int d = 0; d < D; ++d) orow[d] = 0.0;
+      if (L == 0) { alpha0[bh] = NAN; max_rest[bh] = NAN; mean_rest[bh] = NAN; continue; }
+      const uint16_t* qh = q + (size_t)bh * D;
+      const uint16_t* K = k_cache + ((size_t)b * Hkv + g) * (size_t)Lmax * D;
+      double top = -INFINITY;
+      for (int32_t t = 0; t < L; ++t) {
+        double s = 0.0;
+        for (int d = 0; d < D; ++d) s += bf16_to_double(qh[d]) * bf16_to_double(K[(size_t)t * D + d]);
+        w[t] = s * scale;
+        if (w[t] > top) top = w[t];
+      }
+      double total = 0.0;
+      for (int32_t t = 0; t < L; ++t) { w[t] = exp(w[t] - top); total += w[t]; }
+      for (int32_t t = 0; t < L; ++t) w[t] /= total;          /* alpha_t */
+      double biggest = 0.0, rest = 0.0;
+      for (int32_t t = 1; t < L; ++t) {
+        if (w[t] > biggest) biggest = w[t];
+        rest += w[t];
+      }
+      alpha0[bh] = w[0];
+      max_rest[bh] = biggest;
+      mean_rest[bh] = L > 1 ? rest / (double)(L - 1) : 0.0;
+      if (orow && L > 1) {
+        const uint16_t* V = v_cache + ((size_t)b * Hkv + g) * (size_t)Lmax * D;
+        for (int32_t t = 1; t < L; ++t)
+          for (int d = 0; d < D; ++d) orow[d] += w[t] * bf16_to_double(V[(size_t)t * D + d]);
+        for (int d = 0; d < D; ++d) orow[d] /= rest;
+      }
+    }
+    free(w);
   }
   return failed ? -3 : 0;
 }

@@ -395,6 +395,50 @@ def check_paged_gather(lib=None):
     assert ref.mask.any() and not ref.mask.all()
 
 
+def check_concentration(lib=None):
+    """Table 1's statistics (Section 3): weight of token 0, largest and mean weight of the rest."""
+    # hand case: q = [1], keys 0, 1, 2, scale ln 2 -> unnormalised weights 1, 2, 4
+    q = bits(np.array([[[1.0]]]))
+    k = bits(np.array([[[[0.0], [1.0], [2.0]]]]))
+    v = bits(np.array([[[[8.0], [1.0], [-2.0]]]]))
+    a0, mx, mean, rest = oracle.concentration(q, k, v, [3], sm_scale=float(np.log(2.0)), libpath=lib)
+    np.testing.assert_allclose([a0[0, 0], mx[0, 0], mean[0, 0]], [1 / 7, 4 / 7, 3 / 7], rtol=1e-14)
+    np.testing.assert_allclose(rest[0, 0, 0], (2 * 1.0 + 4 * -2.0) / 6, rtol=1e-14)
+    # the largest weight may sit on token 0: it must not be reported as the largest of the rest
+    k2 = bits(np.array([[[[3.0], [1.0], [2.0]]]]))
+    a0, mx, mean, _ = oracle.concentration(q, k2, v, [3], sm_scale=float(np.log(2.0)), libpath=lib)
+    np.testing.assert_allclose([a0[0, 0], mx[0, 0], mean[0, 0]], [8 / 14, 4 / 14, 3 / 14], rtol=1e-14)
+    # library softmax on grouped heads with ragged lengths; token 0 dropped for out_rest
+    B, Hq, Hkv, D, Lmax = 3, 6, 2, 8, 19
+    sl = [19, 7, 2]
+    qq, kk, vv, _ = synth.random_small(900, B, Hq, Hkv, D, Lmax, sl)
+    a0, mx, mean, rest = oracle.concentration(qq, kk, vv, sl, libpath=lib)
+    qf = f64(qq)
+    kf = np.repeat(f64(kk), Hq // Hkv, axis=1)
+    for b in range(B):
+        L = sl[b]
+        p = softmax(np.einsum("hd,htd->ht", qf[b], kf[b, :, :L]) / np.sqrt(D), axis=-1)
+        np.testing.assert_allclose(a0[b], p[:, 0], rtol=1e-12)
+        np.testing.assert_allclose(mx[b], p[:, 1:].max(axis=-1), rtol=1e-12)
+        np.testing.assert_allclose(mean[b], p[:, 1:].mean(axis=-1), rtol=1e-12)
+    np.testing.assert_allclose(a0 + mean * (np.asarray(sl)[:, None] - 1), 1.0, rtol=1e-13)
+    assert np.all(mx >= mean - 1e-15)
+    ref, _, _ = library_attention(qq, kk[:, :, 1:], vv[:, :, 1:], np.asarray(sl) - 1)
+    np.testing.assert_allclose(rest, ref, rtol=1e-11, atol=1e-13)
+    # identical keys: every weight is 1/L
+    k_same = np.repeat(kk[:, :, :1], Lmax, axis=2)
+    a0, mx, mean, _ = oracle.concentration(qq, k_same, vv, sl, libpath=lib)
+    for b in range(B):
+        np.testing.assert_allclose(a0[b], 1.0 / sl[b], rtol=1e-13)
+        np.testing.assert_allclose(mx[b], 1.0 / sl[b], rtol=1e-13)
+        np.testing.assert_allclose(mean[b], 1.0 / sl[b], rtol=1e-13)
+    # one token: all the weight on it, nothing else; none: undefined
+    a0, mx, mean, rest = oracle.concentration(qq, kk, vv, [1, 0, 1], libpath=lib)
+    assert np.all(a0[0] == 1.0) and np.all(mx[0] == 0.0) and np.all(mean[0] == 0.0) and np.all(rest[0] == 0.0)
+    assert np.all(np.isnan(a0[1])) and np.all(np.isnan(mx[1])) and np.all(np.isnan(mean[1])) and np.all(rest[1] == 0.0)
+
+
 ALL_PINS = [check_golden, check_brute_force_dense, check_routed_vs_library,
             check_splitk_equals_single_pass, check_closed_forms, check_cosine_properties,
-            check_decision_properties, check_skip_error_bound, check_symmetries, check_separate_anchor, check_paged_gather]
+            check_decision_properties, check_skip_error_bound, check_symmetries, check_separate_anchor, check_paged_gather,
+            check_concentration]

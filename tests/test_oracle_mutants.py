@@ -46,6 +46,12 @@ MUTANTS = [
     ("page_group_stride_wrong", "const uint16_t* src = pages + (((size_t)page * Hkv + g) * page_tokens",
      "const uint16_t* src = pages + (((size_t)page + (size_t)g * n_pages) * page_tokens"),
     ("page_table_row_stride_wrong", "int32_t page = table[(size_t)b * pages_per_seq + j];", "int32_t page = table[(size_t)b + j];"),
+    ("concentration_max_counts_token0", "for (int32_t t = 1; t < L; ++t) {\n        if (w[t] > biggest)",
+     "for (int32_t t = 0; t < L; ++t) {\n        if (w[t] > biggest)"),
+    ("concentration_mean_over_all_tokens", "rest / (double)(L - 1)", "rest / (double)L"),
+    ("concentration_not_normalised", "for (int32_t t = 0; t < L; ++t) w[t] /= total;", ""),
+    ("concentration_rest_not_renormalised", "for (int d = 0; d < D; ++d) orow[d] /= rest;", ""),
+    ("concentration_scale_dropped", "w[t] = s * scale;", "w[t] = s;"),
     ("separate_anchor_wrong_group", "k0_rows + ((size_t)b * Hkv + g) * D", "k0_rows + ((size_t)b * Hkv) * D"),
 ]
 
