@@ -163,6 +163,25 @@ int sinkrouter_decode_diag(const void* q, const void* k_cache, const void* v_cac
                            void* out, uint8_t* skip_mask_out, float* lse_out, float* alpha0_out);
 
 /*
+ * Attention-concentration statistics per head, the quantities of Table 1 (Section 3): with alpha the
+ * softmax weights of the scaled scores over the whole cache (Eq. 1),
+ *   alpha0_out    device fp32 [B,H_q]: alpha_0, the weight of token 0
+ *   max_rest_out  device fp32 [B,H_q]: the largest weight among tokens 1..L-1
+ *   mean_rest_out device fp32 [B,H_q]: the mean weight of tokens 1..L-1
+ *   out_rest      device bf16 [B,H_q,D]: the head update with token 0 left out and the other
+ *                 weights renormalised (what the head would write without its sink token)
+ * (the table's Ratio is alpha0 / max_rest).  Every head is measured: routing_enabled, k0 and
+ * k0_norm of params are ignored and skip_mask_out [B,H_kv] is written as zeros.  One pass over
+ * tokens 1..L-1 with the decode kernels; token 0 is folded in by the merge.  A one-token cache
+ * gives alpha0 = 1, max = mean = 0, out_rest = 0; an empty one gives NaN statistics, out_rest = 0.
+ * Contiguous caches only.  Same workspace, stream and error conventions as sinkrouter_decode.
+ */
+int sinkrouter_concentration(const void* q, const void* k_cache, const void* v_cache,
+                             const int32_t* seq_lens, const sr_route_params* params,
+                             void* out_rest, uint8_t* skip_mask_out,
+                             float* alpha0_out, float* max_rest_out, float* mean_rest_out);
+
+/*
  * Paged KV cache (serving layout; the paper's kernel takes contiguous caches, Section 4.3).
  * Pages hold page_tokens tokens, a power of two >= 64, so a 64-token block never straddles a
  * page; the pools are laid out [n_pages, H_kv, page_tokens, D] bf16.

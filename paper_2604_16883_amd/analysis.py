@@ -84,3 +84,32 @@ def skipped_vs_active_alpha0(alpha0: np.ndarray, mask: np.ndarray, group_size: i
             "active_mean": float(a[~m].mean()) if (~m).any() else float("nan"),
             "skipped_frac_above_gamma": float((a[m] > GAMMA).mean()) if m.any() else float("nan"),
             "active_frac_above_gamma": float((a[~m] > GAMMA).mean()) if (~m).any() else float("nan")}
+
+
+def concentration_table(alpha0, max_rest, mean_rest, regimes: Sequence[float] = (0.4, 0.6, 0.8),
+                        half_width: float = 0.05) -> Dict[float, Dict[str, float]]:
+    """Attention-concentration statistics by sink regime, the layout of Table 1 (Section 3).
+
+    Inputs are the per-head outputs of ``sinkrouter_concentration`` (any shape, flattened).  For
+    each regime value a, the heads with |alpha_0 - a| <= half_width are averaged: ``bos`` (mean
+    alpha_0), ``max`` (mean largest non-initial weight), ``mean`` (mean non-initial weight), and
+    ``ratio`` = bos / max as the table defines it; ``heads`` counts them (NaN rows when none).
+    Reading: the table does not say how wide its "alpha_0 is about a" bins are; half_width is
+    that free choice.
+    """
+    a = np.asarray(alpha0, np.float64).ravel()
+    mx = np.asarray(max_rest, np.float64).ravel()
+    mn = np.asarray(mean_rest, np.float64).ravel()
+    ok = np.isfinite(a) & np.isfinite(mx) & np.isfinite(mn)
+    table = {}
+    for r in regimes:
+        sel = ok & (np.abs(a - r) <= half_width)
+        n = int(sel.sum())
+        if n == 0:
+            table[float(r)] = {"heads": 0, "bos": float("nan"), "max": float("nan"), "mean": float("nan"),
+                               "ratio": float("nan")}
+            continue
+        bos, big = float(a[sel].mean()), float(mx[sel].mean())
+        table[float(r)] = {"heads": n, "bos": bos, "max": big, "mean": float(mn[sel].mean()),
+                           "ratio": bos / big if big > 0 else float("inf")}
+    return table

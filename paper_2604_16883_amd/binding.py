@@ -101,6 +101,8 @@ def load() -> ctypes.CDLL:
         lib.sinkrouter_decode_profiled.restype = ctypes.c_int
         lib.sinkrouter_decode_diag.argtypes = [vp, vp, vp, i32p, pp, vp, vp, vp, vp]
         lib.sinkrouter_decode_diag.restype = ctypes.c_int
+        lib.sinkrouter_concentration.argtypes = [vp, vp, vp, i32p, pp, vp, vp, vp, vp, vp]
+        lib.sinkrouter_concentration.restype = ctypes.c_int
         lib.sinkrouter_decode_paged.argtypes = [vp, vp, vp, vp, i32p, pp, ctypes.POINTER(PagedLayout), vp, vp]
         lib.sinkrouter_decode_paged.restype = ctypes.c_int
         lib.sinkrouter_extract_anchor.argtypes = [vp, pp, vp, vp]
@@ -222,6 +224,19 @@ def sinkrouter_decode_diag(q, k_cache, v_cache, seq_lens, route_params: RoutePar
                                        _addr(out), _addr(skip_mask_out), _addr(lse_out), _addr(alpha0_out))
     if check and rc != SR_OK:
         raise SinkRouterError(rc, "sinkrouter_decode_diag")
+    return rc
+
+
+def sinkrouter_concentration(q, k_cache, v_cache, seq_lens, route_params: RouteParams, out_rest, skip_mask_out,
+                             alpha0_out, max_rest_out, mean_rest_out, check: bool = True) -> int:
+    """Per-head weight of token 0, largest and mean weight of the other tokens, and the head update
+    without token 0 (Section 3, Table 1); routing is ignored."""
+    p = _with_stream(route_params)
+    rc = load().sinkrouter_concentration(_addr(q), _addr(k_cache), _addr(v_cache), _addr(seq_lens), ctypes.byref(p),
+                                         _addr(out_rest), _addr(skip_mask_out), _addr(alpha0_out),
+                                         _addr(max_rest_out), _addr(mean_rest_out))
+    if check and rc != SR_OK:
+        raise SinkRouterError(rc, "sinkrouter_concentration")
     return rc
 
 

@@ -633,6 +633,11 @@ struct CombineArgs {
   float* lse_out;
   float* alpha0_out;
   float scale_log2;
+  // concentration mode (max_rest_out set): the partials cover tokens 1..L-1 of the cache whose row 0
+  // is at k; token 0 is folded in here.  lens_full holds the unshifted lengths.
+  const int32_t* lens_full;
+  float* max_rest_out;
+  float* mean_rest_out;
 };
 
 __global__ __launch_bounds__(kCombineThreads) void sr_combine_kernel(CombineArgs a) {
@@ -656,8 +661,16 @@ __global__ __launch_bounds__(kCombineThreads) void sr_combine_kernel(CombineArgs
   if (n == 0) {                                  // zero surrogate (Eq. 11) / empty sequence
     if (wave == 0) orow[lane] = 0u;
     if (threadIdx.x == 0) {                      // not computed for Sink Groups; an empty row has lse = -inf
-      if (a.lse_out) a.lse_out[bh] = (L == 0) ? -INFINITY : __int_as_float(0x7fc00000);
-      if (a.alpha0_out) a.alpha0_out[bh] = __int_as_float(0x7fc00000);
+      const float nan = __int_as_float(0x7fc00000);
+      if (a.max_rest_out) {                      // a one-token cache has all its weight on token 0
+        const bool one = clamp_len(a.lens_full[b], a.Lmax) == 1;
+        a.alpha0_out[bh] = one ? 1.f : nan;
+        a.max_rest_out[bh] = one ? 0.f : nan;
+        a.mean_rest_out[bh] = one ? 0.f : nan;
+      } else {
+        if (a.lse_out) a.lse_out[bh] = (L == 0) ? -INFINITY : nan;
+        if (a.alpha0_out) a.alpha0_out[bh] = nan;
+      }
     }
     return;
   }
@@ -714,11 +727,28 @@ __global__ __launch_bounds__(kCombineThreads) void sr_combine_kernel(CombineArgs
         float d = bf16_lo(qw) * bf16_lo(kw) + bf16_hi(qw) * bf16_hi(kw);
 #pragma unroll
         for (int o = 32; o >= 1; o >>= 1) d += __shfl_xor(d, o, 64);
-        if (lane == 0) a.alpha0_out[bh] = __builtin_amdgcn_exp2f(d * a.scale_log2 - lse2);
+        if (a.max_rest_out) {                                           // Table 1 (Section 3): lse2 and M are those of tokens >= 1
+          const float z0 = d * a.scale_log2;
+          const float hi = fmaxf(z0, lse2);
+          const float full = hi + __builtin_amdgcn_logf(__builtin_amdgcn_exp2f(z0 - hi) + __builtin_amdgcn_exp2f(lse2 - hi));
+          if (lane == 0) {
+            a.alpha0_out[bh] = __builtin_amdgcn_exp2f(z0 - full);
+            a.max_rest_out[bh] = __builtin_amdgcn_exp2f(M - full);
+            a.mean_rest_out[bh] = __builtin_amdgcn_exp2f(lse2 - full) / (float)L;
+          }
+        } else if (lane == 0) {
+          a.alpha0_out[bh] = __builtin_amdgcn_exp2f(d * a.scale_log2 - lse2);
+        }
       }
       if (a.lse_out && lane == 0) a.lse_out[bh] = lse2 * 0.6931471805599453f;
     }
   }
+}
+
+// Lengths of the caches with token 0 taken off, for the concentration statistics.
+__global__ __launch_bounds__(256) void sr_rest_lens_kernel(const int32_t* seq_lens, int32_t* rest, int B, int Lmax) {
+  const int b = blockIdx.x * 256 + threadIdx.x;
+  if (b < B) rest[b] = max(clamp_len(seq_lens[b], Lmax) - 1, 0);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -768,7 +798,7 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct Layout {
   sr_plan plan;
-  size_t off_o, off_ml, off_score, off_sched;
+  size_t off_o, off_ml, off_score, off_sched, off_lens;
 };
 
 int make_layout(const sr_route_params* p, Layout* lay) {
@@ -820,7 +850,8 @@ int make_layout(const sr_route_params* p, Layout* lay) {
   lay->off_ml = align_up(heads * S * kD * sizeof(float), 256);
   lay->off_score = lay->off_ml + align_up(heads * S * 2 * sizeof(float), 256);
   lay->off_sched = lay->off_score + align_up((size_t)NG * sizeof(float), 256);
-  pl.workspace_bytes = lay->off_sched + align_up((size_t)(NG + 3) * sizeof(int32_t), 256);
+  lay->off_lens = lay->off_sched + align_up((size_t)(NG + 3) * sizeof(int32_t), 256);
+  pl.workspace_bytes = lay->off_lens + align_up((size_t)p->batch * sizeof(int32_t), 256);
   return SR_OK;
 }
 
@@ -851,15 +882,23 @@ int launch_probe(const void* q, const void* k, const int32_t* seq_lens, const sr
   return hipGetLastError() == hipSuccess ? SR_OK : SR_ERR_HIP;
 }
 
+// Outputs of the concentration statistics; decode_impl then attends over tokens 1..L-1 only.
+struct RestStats {
+  float* max_rest;
+  float* mean_rest;
+};
+
 int decode_impl(const void* q, const void* k, const void* v, const int32_t* seq_lens,
                 const sr_route_params* p, void* out, uint8_t* mask, float* stage_us,
-                float* lse_out = nullptr, float* alpha0_out = nullptr, const PageMap* pages = nullptr) {
+                float* lse_out = nullptr, float* alpha0_out = nullptr, const PageMap* pages = nullptr,
+                const RestStats* rest = nullptr) {
   if (!q || !k || !v || !seq_lens || !p || !out || !mask) return SR_ERR_NULL;
   Layout lay;
   int rc = make_layout(p, &lay);
   if (rc != SR_OK) return rc;
   if (misaligned(q, 16) || misaligned(k, 16) || misaligned(v, 16) || misaligned(out, 16) || misaligned(seq_lens, 4) ||
-      misaligned(p->k0, 16) || misaligned(p->k0_norm, 4) || misaligned(lse_out, 4) || misaligned(alpha0_out, 4))
+      misaligned(p->k0, 16) || misaligned(p->k0_norm, 4) || misaligned(lse_out, 4) || misaligned(alpha0_out, 4) ||
+      (rest && (misaligned(rest->max_rest, 4) || misaligned(rest->mean_rest, 4))))
     return SR_ERR_ALIGN;
   if (!p->workspace || misaligned(p->workspace, 256) || p->workspace_bytes < lay.plan.workspace_bytes)
     return SR_ERR_WORKSPACE;
@@ -874,6 +913,19 @@ int decode_impl(const void* q, const void* k, const void* v, const int32_t* seq_
   if (pages) pm = *pages;
   const bool paged = pm.table != nullptr;
   const bool fused = balanced && (int64_t)p->batch * p->n_q_heads <= kMaxFusedHeads;
+  // Concentration statistics: the caches are entered one row later with lengths one shorter, so the
+  // partial kernels see tokens 1..L-1 (row L-1 is the last one read, as in a plain call).
+  const void* k_anchor = k;
+  const int32_t* lens_full = seq_lens;
+  if (rest) {
+    int32_t* lens_rest = reinterpret_cast<int32_t*>(ws + lay.off_lens);
+    hipLaunchKernelGGL(sr_rest_lens_kernel, dim3((p->batch + 255) / 256), dim3(256), 0, st, seq_lens, lens_rest,
+                       p->batch, p->max_seq_len);
+    if (hipGetLastError() != hipSuccess) return SR_ERR_HIP;
+    seq_lens = lens_rest;
+    k = static_cast<const uint16_t*>(k) + kD;
+    v = static_cast<const uint16_t*>(v) + kD;
+  }
 
   hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
   if (stage_us) {
@@ -885,7 +937,7 @@ int decode_impl(const void* q, const void* k, const void* v, const int32_t* seq_
   }
   auto mark = [&](int i) { return !stage_us || hipEventRecord(ev[i], st) == hipSuccess; };
   bool ok = mark(0);
-  if (ok && !fused) ok = launch_probe(q, k, seq_lens, p, lay, score, mask, st, pm) == SR_OK;
+  if (ok && !fused) ok = launch_probe(q, k_anchor, seq_lens, p, lay, score, mask, st, pm) == SR_OK;
   if (ok) ok = mark(1);
   if (ok) {
     PartialArgs a;
@@ -913,8 +965,11 @@ int decode_impl(const void* q, const void* k, const void* v, const int32_t* seq_
   if (ok) ok = mark(2);
   if (ok) {
     CombineArgs c;
-    c.q = static_cast<const uint32_t*>(q); c.k = k;
+    c.q = static_cast<const uint32_t*>(q); c.k = k_anchor;
     c.lse_out = lse_out; c.alpha0_out = alpha0_out; c.scale_log2 = scale_log2;
+    c.lens_full = lens_full;
+    c.max_rest_out = rest ? rest->max_rest : nullptr;
+    c.mean_rest_out = rest ? rest->mean_rest : nullptr;
     c.part_o = part_o; c.part_ml = part_ml; c.seq_lens = seq_lens; c.mask = mask;
     c.sched = balanced ? sched : nullptr;
     c.out = static_cast<uint32_t*>(out);
@@ -991,6 +1046,20 @@ int sinkrouter_decode_diag(const void* q, const void* k_cache, const void* v_cac
                            float* lse_out, float* alpha0_out) {
   if (!lse_out && !alpha0_out) return SR_ERR_NULL;
   return decode_impl(q, k_cache, v_cache, seq_lens, params, out, skip_mask_out, nullptr, lse_out, alpha0_out);
+}
+
+int sinkrouter_concentration(const void* q, const void* k_cache, const void* v_cache, const int32_t* seq_lens,
+                             const sr_route_params* params, void* out_rest, uint8_t* skip_mask_out,
+                             float* alpha0_out, float* max_rest_out, float* mean_rest_out) {
+  if (!params || !alpha0_out || !max_rest_out || !mean_rest_out) return SR_ERR_NULL;
+  if (params->struct_size != sizeof(sr_route_params)) return SR_ERR_UNSUPPORTED;
+  sr_route_params dense = *params;              // every head is measured: no routing, no cached anchors
+  dense.routing_enabled = 0;
+  dense.k0 = nullptr;
+  dense.k0_norm = nullptr;
+  const RestStats rest = {max_rest_out, mean_rest_out};
+  return decode_impl(q, k_cache, v_cache, seq_lens, &dense, out_rest, skip_mask_out, nullptr, nullptr, alpha0_out,
+                     nullptr, &rest);
 }
 
 int sinkrouter_decode_paged(const void* q, const void* k_pages, const void* v_pages, const int32_t* block_table,

@@ -68,7 +68,7 @@ def test_plan_balanced(name):
     assert pl.slots_per_head == min(blocks, 257)
     heads = b * hq
     need = heads * pl.slots_per_head * (128 + 2) * 4
-    assert need <= pl.workspace_bytes <= need + 4096 + 8 * (b * hkv + 3) + 4 * b * hkv + 1024
+    assert need <= pl.workspace_bytes <= need + 4096 + 8 * (b * hkv + 3) + 4 * b * hkv + 4 * b + 1280
     assert B.sinkrouter_workspace_bytes(B.make_route_params(b, hq, hkv, L)) == pl.workspace_bytes
 
 
@@ -109,6 +109,13 @@ def test_null_pointers_are_rejected():
     assert B.sinkrouter_probe(None, FAKE["k"], FAKE["sl"], p, None, FAKE["mask"], check=False) == B.SR_ERR_NULL
     assert B.sinkrouter_probe(FAKE["q"], FAKE["k"], FAKE["sl"], p, None, None, check=False) == B.SR_ERR_NULL
     assert lib.sinkrouter_hbm_read_probe(None, 1024, 1 << 16, None) == B.SR_ERR_NULL
+    # concentration statistics: all three statistic outputs are required, then the decode checks apply
+    cargs = [FAKE["q"], FAKE["k"], FAKE["v"], FAKE["sl"], p, FAKE["out"], FAKE["mask"]]
+    assert B.sinkrouter_concentration(*cargs, 1 << 22, None, 1 << 23, check=False) == B.SR_ERR_NULL
+    assert B.sinkrouter_concentration(*cargs, None, 1 << 22, 1 << 23, check=False) == B.SR_ERR_NULL
+    assert B.sinkrouter_concentration(FAKE["q"], None, FAKE["v"], FAKE["sl"], p, FAKE["out"], FAKE["mask"],
+                                      1 << 22, 1 << 23, 1 << 24, check=False) == B.SR_ERR_NULL
+    assert B.sinkrouter_concentration(*cargs, 1 << 22, (1 << 23) + 2, 1 << 24, check=False) == B.SR_ERR_ALIGN
     assert lib.sinkrouter_hbm_copy_probe(1 << 16, None, 1024, None) == B.SR_ERR_NULL
 
 

@@ -103,3 +103,36 @@ def test_calibrate_end_to_end_with_oracle_scores():
     sb = synth.generate(synth.WORKLOADS["c1"].scaled(1024), seed=500)
     r = oracle.route(sb.q, sb.k, sb.seq_lens, tau_coef=cal["tau_coef"], len_norm=cal["len_norm"])
     assert r.tau[0] == pytest.approx(cal["per_length_tau"][2], abs=1e-9)
+
+
+def test_concentration_table_bins_and_ratio():
+    a0 = np.array([0.41, 0.39, 0.62, 0.8, 0.83, 0.2, np.nan])
+    mx = np.array([0.02, 0.04, 0.031, 0.01, 0.03, 0.5, 0.1])
+    mn = np.array([1e-4, 3e-4, 2e-4, 1e-5, 3e-5, 1e-3, 1e-3])
+    t = analysis.concentration_table(a0, mx, mn)
+    assert [t[k]["heads"] for k in (0.4, 0.6, 0.8)] == [2, 1, 2]
+    assert t[0.4]["bos"] == pytest.approx(0.40) and t[0.4]["max"] == pytest.approx(0.03)
+    assert t[0.4]["mean"] == pytest.approx(2e-4) and t[0.4]["ratio"] == pytest.approx(0.40 / 0.03)
+    assert t[0.6]["ratio"] == pytest.approx(0.62 / 0.031)
+    assert t[0.8]["ratio"] == pytest.approx(0.815 / 0.02)
+    empty = analysis.concentration_table(a0, mx, mn, regimes=(0.95,), half_width=0.01)
+    assert empty[0.95]["heads"] == 0 and np.isnan(empty[0.95]["ratio"])
+
+
+def test_concentration_table_on_oracle_statistics_orders_the_regimes():
+    """Graded pull toward token 0 fills the regimes of Table 1 (Section 3); the ratio of the token-0
+    weight to the strongest other weight grows with the regime, the table's qualitative content."""
+    import dataclasses
+    cols = []
+    for i, gain in enumerate((9.0, 12.0, 15.0)):
+        w = dataclasses.replace(synth.WORKLOADS["c0"].scaled(600), sink_gain=gain, sink_frac=1.0, planted_per_head=0)
+        sb = synth.generate(w, seed=70 + i)
+        a0, mx, mean, _ = oracle.concentration(sb.q, sb.k, sb.v, sb.seq_lens)
+        np.testing.assert_allclose(a0 + mean * (600 - 1), 1.0, rtol=1e-12)
+        cols.append((a0.ravel(), mx.ravel(), mean.ravel()))
+    cat = [np.concatenate([c[j] for c in cols]) for j in range(3)]
+    t = analysis.concentration_table(*cat, half_width=0.1)
+    filled = [k for k in sorted(t) if t[k]["heads"] > 0]
+    assert len(filled) >= 2
+    ratios = [t[k]["ratio"] for k in filled]
+    assert all(a < b for a, b in zip(ratios, ratios[1:]))
