@@ -46,8 +46,8 @@ typedef enum sr_status {
  * Shape, routing rule and launch resources of one call.  Plain data, host memory.
  *
  * Routing rule (Section 4.2): for KV group g of sequence b with r = n_q_heads / n_kv_heads
- * query heads, s_i = cos(q_{g,i}, K_0) (Eq. 8), S_g = mean_i s_i (Eq. 9), and the group is a
- * Sink Group iff S_g > tau(L_b), strictly (Eq. 10), with the length-dependent threshold
+ * query heads, s_i = cos(q_{g,i}, K_0) (Eq. 11), S_g = mean_i s_i (Eq. 12), and the group is a
+ * Sink Group iff S_g > tau(L_b), strictly (Eq. 13), with the length-dependent threshold
  * tau(x) = a x^3 + b x^2 + c x + d of Appendix A evaluated at x = seq_lens[b] / len_norm.
  * The paper prints neither the coefficients nor the normalisation, so both are inputs; a
  * fixed threshold t is {0,0,0,t} (the paper's operating point is 0.55).  K_0 is row 0 of the
@@ -106,7 +106,7 @@ int sinkrouter_plan(const sr_route_params* params /*host*/, sr_plan* plan /*host
 size_t sinkrouter_workspace_bytes(const sr_route_params* params /*host*/);
 
 /*
- * One routed decode step (Sections 4.2-4.3; Eq. 1 for Active Groups, Eq. 11 for Sink Groups).
+ * One routed decode step (Sections 4.2-4.3; Eq. 1 for Active Groups, Eq. 14 for Sink Groups).
  *   q             device bf16 [B,H_q,D]; head h belongs to KV group h / r (the paper's
  *                 [B,H_kv,G,D] layout, same memory)
  *   k_cache       device bf16 [B,H_kv,L_max,D]
@@ -129,7 +129,7 @@ int sinkrouter_decode(const void* q, const void* k_cache, const void* v_cache,
                       void* out, uint8_t* skip_mask_out);
 
 /*
- * The routing decision alone (Section 4.2, Eq. 8-10): reads q and row 0 of k_cache only.
+ * The routing decision alone (Section 4.2, Eq. 11-13): reads q and row 0 of k_cache only.
  *   group_score_out device fp32 [B,H_kv], optional: S_g
  *   skip_mask_out   device uint8 [B,H_kv]
  * Needs no workspace.

@@ -9,11 +9,11 @@
  * What is written out here, with the passage of the paper each part follows:
  *   - head update u = sum_i alpha_i v_i, alpha = softmax of the scaled
  *     query-key scores                                   (Section 3, Eq. 1)
- *   - per-head routing signal s_{g,i} = cos(q_{g,i}, K_0) (Section 4.2, Eq. 8)
- *   - group score S_g = mean over the r heads of the group (Section 4.2, Eq. 9)
- *   - Sink Group iff S_g > tau(L), strict                 (Section 4.2, Eq. 10)
+ *   - per-head routing signal s_{g,i} = cos(q_{g,i}, K_0) (Section 4.2, Eq. 11)
+ *   - group score S_g = mean over the r heads of the group (Section 4.2, Eq. 12)
+ *   - Sink Group iff S_g > tau(L), strict                 (Section 4.2, Eq. 13)
  *   - tau(x) = a x^3 + b x^2 + c x + d, x = L / len_norm  (Appendix A)
- *   - Sink Groups output zero for all r heads             (Section 4.2, Eq. 11)
+ *   - Sink Groups output zero for all r heads             (Section 4.2, Eq. 14)
  *   - Active Groups: exact standard attention over the available cache
  *                                                         (Section 4.2, last paragraph)
  *   - concentration statistics alpha_0, max and mean of the other weights
@@ -86,7 +86,7 @@ static double tau_of(const sr_oracle_cfg* c, int32_t L) {
   return t[0] * x * x * x + t[1] * x * x + t[2] * x + t[3];
 }
 
-/* Eq. 8: cosine between one query head and the anchor key. */
+/* Eq. 11: cosine between one query head and the anchor key. */
 static double cosine_to_anchor(const uint16_t* q, const uint16_t* k0, int D,
                                double anchor_norm /* <0: recompute */) {
   double dot = 0.0, nq = 0.0, nk = 0.0;
@@ -132,7 +132,7 @@ static void head_partial(const uint16_t* q, const uint16_t* K, const uint16_t* V
 }
 
 /*
- * Routing only (Eq. 8-10).  All outputs optional except mask.  k0_rows (optional) overrides
+ * Routing only (Eq. 11-13).  All outputs optional except mask.  k0_rows (optional) overrides
  * the anchors read from row 0 of k_cache.
  *   head_cos    [B,H_q]   s_{g,i}
  *   group_score [B,H_kv]  S_g
@@ -209,7 +209,7 @@ int sr_oracle_decode(const uint16_t* q, const uint16_t* k_cache, const uint16_t*
       double* orow = out + (size_t)bh * D;
       double* drow = dense_out ? dense_out + (size_t)bh * D : NULL;
       if (skip && !c->want_dense) {
-        for (int d = 0; d < D; ++d) orow[d] = 0.0;          /* Eq. 11 */
+        for (int d = 0; d < D; ++d) orow[d] = 0.0;          /* Eq. 14 */
         if (drow) for (int d = 0; d < D; ++d) drow[d] = NAN;
         if (alpha0) alpha0[bh] = NAN;
         if (lse) lse[bh] = NAN;

@@ -8,7 +8,7 @@ The inputs here are what the library emits: group scores from ``sinkrouter_probe
 alpha_0 from ``sinkrouter_decode_diag`` run with routing disabled.
 
 Reading: the paper does not say how the group's "full-attention BOS score" is formed from its
-heads; the mean of alpha_0 over the group's heads is used, mirroring the mean in Eq. 9.
+heads; the mean of alpha_0 over the group's heads is used, mirroring the mean in Eq. 12.
 """
 from __future__ import annotations
 
@@ -57,7 +57,7 @@ def average_precision(scores, labels) -> float:
 
 
 def threshold_sweep(scores, labels, taus) -> Dict[str, np.ndarray]:
-    """Precision, recall, F1 and skip ratio of the decision "S_g > tau" (strict, Eq. 10) per tau."""
+    """Precision, recall, F1 and skip ratio of the decision "S_g > tau" (strict, Eq. 13) per tau."""
     s = np.asarray(scores, np.float64).ravel()
     y = np.asarray(labels, bool).ravel()
     out = {k: [] for k in ("tau", "precision", "recall", "f1", "skip_ratio")}

@@ -9,7 +9,7 @@ context length, tau(x) = a x^3 + b x^2 + c x + d, whose coefficients go into
 Readings: the paper does not define the normalisation; x = L / len_norm with len_norm defaulting to
 the largest calibrated length.  With n scores the realised ratio is quantised to multiples of 1/n:
 the threshold is placed midway between the k-th and (k+1)-th largest score, k = round(target * n),
-so exactly k groups exceed it (strict comparison of Eq. 10).
+so exactly k groups exceed it (strict comparison of Eq. 13).
 """
 from __future__ import annotations
 

@@ -1,7 +1,7 @@
 // SinkRouter decode attention for MI355X (gfx950, CDNA4): kernels and the C ABI.
 //
 // Kernels of one decode step, all on the caller's stream:
-//   sr_probe_kernel    routing signal of Section 4.2 (Eq. 8-10): one wavefront per
+//   sr_probe_kernel    routing signal of Section 4.2 (Eq. 11-13): one wavefront per
 //                      (sequence, KV group), four lanes per query head; reads the group's query
 //                      heads and token 0 of K only.  Normally fused into the balanced partial
 //                      kernel (every workgroup evaluates the rule for all groups itself); launched
@@ -24,7 +24,7 @@
 //                  workgroup per (chunk, sequence, KV group); workgroups of Sink Groups
 //                  leave at once.
 //   sr_combine_kernel  log-sum-exp merge of the partials, bf16 output; zeros for Sink Groups
-//                      (Eq. 11).
+//                      (Eq. 14).
 //
 // Register layout of the MFMA shape used for both products (lane = 0..63, r16 = lane % 16, kg = lane / 16):
 //   v_mfma_f32_16x16x32_bf16  A: row r16, 8 consecutive k of k-group kg; B: column r16, same k;
@@ -149,7 +149,7 @@ __device__ __forceinline__ float quad_sumsq(const uint4 (&kw)[4]) {
   return quad_swap_add<0x4E>(kk);
 }
 
-// Eq. 8 for one head; qw / kw are this lane's four chunks of the query and of K_0.
+// Eq. 11 for one head; qw / kw are this lane's four chunks of the query and of K_0.
 // anchor_norm < 0 means "recompute ||K_0||".  All 4 lanes of the head must be active.
 __device__ __forceinline__ float head_cosine(const uint4 (&qw)[4], const uint4 (&kw)[4], float anchor_norm) {
   float dot = 0.f, qq = 0.f;
@@ -170,7 +170,7 @@ __device__ __forceinline__ float head_cosine(const uint4 (&qw)[4], const uint4 (
   return (den > 0.f) ? dot / den : 0.f;
 }
 
-// Eq. 9-10 and the cubic threshold of Appendix A.  cosines: the G values of the group, in head order.
+// Eq. 12-13 and the cubic threshold of Appendix A.  cosines: the G values of the group, in head order.
 __device__ __forceinline__ bool route_decide(const float* cosines, int G, int L, const RouteRule& r, float* S_out) {
   float S = 0.f;
   for (int j = 0; j < G; ++j) S += cosines[j];
@@ -658,7 +658,7 @@ __global__ __launch_bounds__(kCombineThreads) void sr_combine_kernel(CombineArgs
       n = (L + a.chunk - 1) / a.chunk;
     }
   }
-  if (n == 0) {                                  // zero surrogate (Eq. 11) / empty sequence
+  if (n == 0) {                                  // zero surrogate (Eq. 14) / empty sequence
     if (wave == 0) orow[lane] = 0u;
     if (threadIdx.x == 0) {                      // not computed for Sink Groups; an empty row has lse = -inf
       const float nan = __int_as_float(0x7fc00000);

@@ -9,7 +9,7 @@ What fixes the expected values:
   * scipy/numpy library routines (softmax, logsumexp, einsum) on fp64 copies of
     the inputs with the KV heads explicitly repeated per query head;
   * closed forms and invariances that follow from Section 3 Eq. 1, Eq. 3-5 and
-    Section 4.2 Eq. 8-11 of the paper.
+    Section 4.2 Eq. 11-14 of the paper.
 """
 from __future__ import annotations
 
