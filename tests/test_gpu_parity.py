@@ -157,3 +157,40 @@ def test_full_size(name):
     _check(sb, label=name + "-full")
     _check(sb, taus=[0.55], label=name + "-full-dense", routing_enabled=False)
     _check(sb, taus=[0.55], label=name + "-full-fixed-chunks", num_splits=200)
+
+
+# ---- the longest cache the library accepts ---------------------------------------------------------
+def test_maximum_sequence_length():
+    """max_seq_len = 2^24 tokens (the documented limit), one KV group of two heads: 8.6 GB of K and V.
+    Exercises the 64-bit row offsets and the 32-bit token arithmetic at their largest values; the
+    length is one short of the stride so the tail is ragged too."""
+    import time
+    L = (1 << 24) - 1
+    w = synth.Workload("max_len", 1, 2, 1, L, 0.5, base_seed=7000, planted_per_head=16)
+    t0 = time.time()
+    sb = synth.generate(w, max_seq_len=1 << 24)
+    print("max_len generated in %.1f s" % (time.time() - t0), flush=True)
+    res = gu.run_hip(sb.q, sb.k, sb.v, sb.seq_lens, tau_coef=(0, 0, 0, 2.0))
+    print("max_len gpu done", flush=True)
+    t0 = time.time()
+    ref = oracle.decode(sb.q, sb.k, sb.v, sb.seq_lens, tau_coef=(0, 0, 0, 2.0), want_dense=True)
+    print("max_len oracle %.1f s" % (time.time() - t0), flush=True)
+    rep = gu.compare(res, ref, 2, "max_len")
+    pl = res["plan"]
+    assert pl.schedule == 1 and pl.slots_per_head == 257
+    assert not res["mask"].any()
+    print("max_len", rep, flush=True)
+
+
+def test_maximum_group_count():
+    """65535 (sequence, KV group) pairs, the documented limit (fixed chunks, separate probe kernel),
+    with ragged lengths 0..70 on plain Gaussian data: about half the groups are Sink Groups at tau = 0."""
+    B, L = 65535, 70
+    lens = (np.arange(B) * 37) % (L + 1)
+    q, k, v, sl = synth.random_small(7100, B, 1, 1, 128, L, lens)
+    res = gu.run_hip(q, k, v, sl, tau_coef=(0, 0, 0, 0.0))
+    assert res["plan"].schedule == 0 and res["plan"].partial_grid == B * res["plan"].num_splits
+    ref = oracle.decode(q, k, v, sl, tau_coef=(0, 0, 0, 0.0), want_dense=True)
+    rep = gu.compare(res, ref, 1, "65535 groups")
+    print("65535 groups", rep, flush=True)
+    assert 0.3 < rep["skip_ratio"] < 0.7
