@@ -532,7 +532,10 @@ __global__ __launch_bounds__(kThreads, 2) void sr_partial_balanced_kernel(Partia
   // share index = workgroup index: the stream has no reuse, so which XCD works on which share is
   // immaterial (giving each XCD one contiguous eighth of the blocks measured the same)
   const int p = blockIdx.x, P = gridDim.x;
-  for (int i = tid; i < NG; i += kThreads) lens[i] = clamp_len(a.seq_lens[i / a.Hkv], a.Lmax);
+  // the first length load is issued here and parked in a register, so that it and the probe's query /
+  // anchor loads are in flight together (one memory round trip at kernel start instead of two)
+  int len_first = 0;
+  if (tid < NG) len_first = a.seq_lens[tid / a.Hkv];
   if (kFused && a.rule.routing) {
     const int NH = NG * G, lane4 = tid & 3;
     const uint4* q4 = reinterpret_cast<const uint4*>(a.q);
@@ -558,6 +561,8 @@ __global__ __launch_bounds__(kThreads, 2) void sr_partial_balanced_kernel(Partia
       }
     }
   }
+  if (tid < NG) lens[tid] = clamp_len(len_first, a.Lmax);
+  for (int i = tid + kThreads; i < NG; i += kThreads) lens[i] = clamp_len(a.seq_lens[i / a.Hkv], a.Lmax);
   __syncthreads();
   int carry = 0;
   for (int base = 0; base < NG; base += kThreads) {
