@@ -1,5 +1,7 @@
 """Seeded random sweep of shapes, ragged lengths, thresholds, schedules and cache layouts: HIP path vs
 the CPU oracle (needs an MI355X).  Sizes are small so the oracle stays fast; every case is printed."""
+import os
+
 import numpy as np
 import pytest
 
@@ -14,7 +16,10 @@ from test_gpu_paged import run_paged
 GROUPINGS = [(1, 1), (2, 1), (4, 2), (8, 2), (32, 8), (16, 16), (40, 40), (5, 5), (24, 3), (16, 1), (14, 2), (64, 8)]
 
 
-@pytest.mark.parametrize("case", range(36))
+N_CASES = int(os.environ.get("SR_RANDOM_CASES", "36"))     # a longer sweep: SR_RANDOM_CASES=600 pytest ...
+
+
+@pytest.mark.parametrize("case", range(N_CASES))
 def test_random_case(case):
     rng = np.random.default_rng(10_000 + case)
     Hq, Hkv = GROUPINGS[case % len(GROUPINGS)]
