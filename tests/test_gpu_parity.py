@@ -194,3 +194,55 @@ def test_maximum_group_count():
     rep = gu.compare(res, ref, 1, "65535 groups")
     print("65535 groups", rep, flush=True)
     assert 0.3 < rep["skip_ratio"] < 0.7
+
+
+def test_degenerate_routing_inputs():
+    """The degenerate cases of the routing rule, where the decision must be exact and not merely
+    within the band: a zero anchor or zero query (cosine 0, not NaN), an exact tie S == tau (strict
+    comparison keeps the group active), a cached norm of zero, and a NaN anchor (group stays active)."""
+    B, Hq, Hkv, L = 1, 8, 4, 200
+    q, k, v, sl = synth.random_small(7200, B, Hq, Hkv, 128, L)
+    k = k.copy()
+    q = q.copy()
+    k[0, 0, 0] = 0                       # group 0: K_0 = 0  -> every cosine 0, S = 0 exactly
+    q[0, 2] = 0                          # group 1, first head: q = 0 -> its cosine is 0
+    q[0, 4] = k[0, 2, 0]                 # group 2: both heads equal the anchor -> S = 1 up to rounding
+    q[0, 5] = k[0, 2, 0]
+    for tau, want0 in ((0.0, 0), (-1e-6, 1)):          # tie at S == tau == 0: active; just below: Sink Group
+        res = gu.run_hip(q, k, v, sl, tau_coef=(0, 0, 0, tau))
+        ref = oracle.decode(q, k, v, sl, tau_coef=(0, 0, 0, tau), want_dense=True)
+        assert res["score"][0, 0] == 0.0 and ref.group_score[0, 0] == 0.0
+        assert res["mask"][0, 0] == want0 == ref.mask[0, 0]
+        assert np.isfinite(res["score"]).all()
+        gu.compare(res, ref, 2, "degenerate tau=%g" % tau)
+    res = gu.run_hip(q, k, v, sl, tau_coef=(0, 0, 0, 0.999))
+    ref = oracle.decode(q, k, v, sl, tau_coef=(0, 0, 0, 0.999), want_dense=True)
+    assert res["mask"][0].tolist() == [0, 0, 1, 0] == ref.mask[0].tolist()
+    np.testing.assert_allclose(res["score"][0, 1], 0.5 * ref.head_cos[0, 3], rtol=0, atol=2e-6)   # the zero query counts as 0
+    # cached norm of zero: the denominator vanishes, cosines are 0, nothing exceeds tau = 0
+    zero = np.zeros((B, Hkv), np.float32)
+    res = gu.run_hip(q, k, v, sl, tau_coef=(0, 0, 0, 0.0), k0_norm=zero)
+    ref = oracle.decode(q, k, v, sl, tau_coef=(0, 0, 0, 0.0), k0_norm=zero, want_dense=True)
+    assert not res["mask"].any() and not ref.mask.any() and np.all(res["score"] == 0.0)
+    gu.compare(res, ref, 2, "zero cached norm")
+    # NaN in a separately cached anchor whose cached norm is finite: the dot product and so the score
+    # are NaN, the comparison is false, the group stays active.  (Without a cached norm the norm is
+    # NaN too, the denominator test fails and the cosine is 0, on both sides.)
+    import torch
+    k0 = k[:, :, 0].copy()
+    k0[0, 3, 7] = 0x7FC0
+    k0_dev = gu.to_dev(k0)
+    kn = np.linalg.norm(synth.bf16_bits_to_f32(k[:, :, 0]).astype(np.float64), axis=-1)
+    kn[0, 0] = 1.0
+    res = gu.run_hip(q, k, v, sl, tau_coef=(0, 0, 0, -2.0), k0=k0_dev, k0_norm=kn)
+    ref = oracle.decode(q, k, v, sl, tau_coef=(0, 0, 0, -2.0), k0=k0, k0_norm=kn, want_dense=True)
+    assert res["mask"][0].tolist() == [1, 1, 1, 0] == ref.mask[0].tolist()
+    assert np.isnan(res["score"][0, 3]) and np.isnan(ref.group_score[0, 3])
+    assert np.all(res["out_bits"][0, :6] == 0)
+    err = np.abs(res["out"][0, 6:].astype(np.float64) - ref.out[0, 6:])
+    assert err.max() <= gu.MAX_ABS_TOL
+    res = gu.run_hip(q, k, v, sl, tau_coef=(0, 0, 0, -2.0), k0=k0_dev)
+    ref = oracle.decode(q, k, v, sl, tau_coef=(0, 0, 0, -2.0), k0=k0, want_dense=True)
+    assert res["mask"][0].tolist() == [1, 1, 1, 1] == ref.mask[0].tolist()
+    assert res["score"][0, 3] == 0.0 == ref.group_score[0, 3]
+    torch.cuda.synchronize()
