@@ -246,3 +246,22 @@ def test_degenerate_routing_inputs():
     assert res["mask"][0].tolist() == [1, 1, 1, 1] == ref.mask[0].tolist()
     assert res["score"][0, 3] == 0.0 == ref.group_score[0, 3]
     torch.cuda.synchronize()
+
+
+def test_threshold_inside_the_rounding_band():
+    """A threshold closer to a group's score than fp32 can resolve: either decision is accepted for
+    that group, it is counted, and the output must match the oracle's under the decision the GPU
+    took (zeros, or the dense result)."""
+    w = synth.WORKLOADS["c0"].scaled(1000)
+    sb = synth.generate(w, seed=11)
+    scores = oracle.route(sb.q, sb.k, sb.seq_lens).group_score[0]
+    hits = 0
+    for g in range(w.n_kv_heads):
+        for delta in (-2e-8, 2e-8):
+            tau = float(scores[g] + delta)
+            res = gu.run_hip(sb.q, sb.k, sb.v, sb.seq_lens, tau_coef=(0, 0, 0, tau))
+            ref = oracle.decode(sb.q, sb.k, sb.v, sb.seq_lens, tau_coef=(0, 0, 0, tau), want_dense=True)
+            rep = gu.compare(res, ref, w.group_size, "band g%d %+g" % (g, delta))
+            assert rep["near_threshold"] >= 1
+            hits += rep["mask_disagree_in_band"]
+    print("in-band disagreements:", hits, "of", 2 * w.n_kv_heads, flush=True)
