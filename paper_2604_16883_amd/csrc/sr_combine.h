@@ -1,0 +1,146 @@
+// SinkRouter decode attention for MI355X: log-sum-exp merge of the partials, diagnostics, zero surrogate.
+#ifndef SR_COMBINE_H
+#define SR_COMBINE_H
+
+#include "sr_common.h"
+
+namespace {
+
+// ------------------------------------------------------------------------------------------
+// Merge of the partials.  grid = B*H_q, block = 1024 (16 wavefronts; lane owns 2 columns).
+// ------------------------------------------------------------------------------------------
+struct CombineArgs {
+  const float* part_o;
+  const float* part_ml;
+  const int32_t* seq_lens;
+  const uint8_t* mask;
+  const int32_t* sched;   // balanced schedule, else NULL
+  uint32_t* out;          // bf16 pairs
+  int Hq, Hkv, G, Lmax, chunk, slots;
+  // diagnostics (optional): log-sum-exp of the scaled scores and softmax mass on token 0 per head
+  const uint32_t* q;      // bf16 pairs
+  const void* k;          // contiguous key cache (diagnostics are not offered for paged caches)
+  float* lse_out;
+  float* alpha0_out;
+  float scale_log2;
+  // concentration mode (max_rest_out set): the partials cover tokens 1..L-1 of the cache whose row 0
+  // is at k; token 0 is folded in here.  lens_full holds the unshifted lengths.
+  const int32_t* lens_full;
+  float* max_rest_out;
+  float* mean_rest_out;
+};
+
+__global__ __launch_bounds__(kCombineThreads) void sr_combine_kernel(CombineArgs a) {
+  constexpr int NW = kCombineThreads / 64;
+  constexpr int UN = 8;
+  const int bh = blockIdx.x;
+  const int b = bh / a.Hq, h = bh - b * a.Hq, g = h / a.G;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int L = clamp_len(a.seq_lens[b], a.Lmax);
+  const int bg = b * a.Hkv + g;
+  uint32_t* orow = a.out + (size_t)bh * (kD / 2);
+  int n = 0;                                     // partial records of this head
+  if (!a.mask[bg] && L > 0) {
+    if (a.sched) {
+      const int c = a.sched[1], s0 = a.sched[2 + bg], s1 = a.sched[3 + bg];
+      if (s1 > s0) n = (s1 - 1) / c - s0 / c + 1;
+    } else {
+      n = (L + a.chunk - 1) / a.chunk;
+    }
+  }
+  if (n == 0) {                                  // zero surrogate (Eq. 14) / empty sequence
+    if (wave == 0) orow[lane] = 0u;
+    if (threadIdx.x == 0) {                      // not computed for Sink Groups; an empty row has lse = -inf
+      const float nan = __int_as_float(0x7fc00000);
+      if (a.max_rest_out) {                      // a one-token cache has all its weight on token 0
+        const bool one = clamp_len(a.lens_full[b], a.Lmax) == 1;
+        a.alpha0_out[bh] = one ? 1.f : nan;
+        a.max_rest_out[bh] = one ? 0.f : nan;
+        a.mean_rest_out[bh] = one ? 0.f : nan;
+      } else {
+        if (a.lse_out) a.lse_out[bh] = (L == 0) ? -INFINITY : nan;
+        if (a.alpha0_out) a.alpha0_out[bh] = nan;
+      }
+    }
+    return;
+  }
+  const float2* ml = reinterpret_cast<const float2*>(a.part_ml) + (size_t)bh * a.slots;
+  const float2* po = reinterpret_cast<const float2*>(a.part_o) + (size_t)bh * a.slots * (kD / 2);
+
+  __shared__ float red_m[NW];
+  __shared__ float red_l[NW];
+  __shared__ float2 red_o[NW][64];
+  float mx = -INFINITY;
+  for (int s = threadIdx.x; s < n; s += kCombineThreads) mx = fmaxf(mx, ml[s].x);
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+  if (lane == 0) red_m[wave] = mx;
+  __syncthreads();
+  float M = red_m[0];
+#pragma unroll
+  for (int u = 1; u < NW; ++u) M = fmaxf(M, red_m[u]);
+
+  float2 acc = make_float2(0.f, 0.f);
+  float lsum = 0.f;
+  for (int s0 = wave; s0 < n; s0 += NW * UN) {   // UN rows in flight per wavefront
+    float2 st[UN], o[UN];
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      const int s = s0 + u * NW;
+      const bool ok = s < n;
+      st[u] = ok ? ml[s] : make_float2(-INFINITY, 0.f);
+      o[u] = ok ? po[(size_t)s * (kD / 2) + lane] : make_float2(0.f, 0.f);
+    }
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      const float wt = __builtin_amdgcn_exp2f(st[u].x - M);
+      acc.x += wt * o[u].x;
+      acc.y += wt * o[u].y;
+      lsum += wt * st[u].y;
+    }
+  }
+  red_o[wave][lane] = acc;
+  if (lane == 0) red_l[wave] = lsum;
+  __syncthreads();
+  if (wave == 0) {
+    float2 t = red_o[0][lane];
+    float l = red_l[0];
+#pragma unroll
+    for (int u = 1; u < NW; ++u) { t.x += red_o[u][lane].x; t.y += red_o[u][lane].y; l += red_l[u]; }
+    const float inv = 1.0f / l;
+    orow[lane] = f32_to_bf16_rne(t.x * inv) | (f32_to_bf16_rne(t.y * inv) << 16);
+    if (a.lse_out || a.alpha0_out) {
+      const float lse2 = M + __builtin_amdgcn_logf(l);                  // log2 domain (v_log_f32 is log2)
+      if (a.alpha0_out) {                                               // alpha_0 = exp(z_0 - lse), Section 4.2
+        const uint32_t qw = a.q[(size_t)bh * (kD / 2) + lane];
+        const uint32_t kw = reinterpret_cast<const uint32_t*>(a.k)[(size_t)bg * a.Lmax * (kD / 2) + lane];   // token 0 of the cache itself
+        float d = bf16_lo(qw) * bf16_lo(kw) + bf16_hi(qw) * bf16_hi(kw);
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) d += __shfl_xor(d, o, 64);
+        if (a.max_rest_out) {                                           // Table 1 (Section 3): lse2 and M are those of tokens >= 1
+          const float z0 = d * a.scale_log2;
+          const float hi = fmaxf(z0, lse2);
+          const float full = hi + __builtin_amdgcn_logf(__builtin_amdgcn_exp2f(z0 - hi) + __builtin_amdgcn_exp2f(lse2 - hi));
+          if (lane == 0) {
+            a.alpha0_out[bh] = __builtin_amdgcn_exp2f(z0 - full);
+            a.max_rest_out[bh] = __builtin_amdgcn_exp2f(M - full);
+            a.mean_rest_out[bh] = __builtin_amdgcn_exp2f(lse2 - full) / (float)L;
+          }
+        } else if (lane == 0) {
+          a.alpha0_out[bh] = __builtin_amdgcn_exp2f(d * a.scale_log2 - lse2);
+        }
+      }
+      if (a.lse_out && lane == 0) a.lse_out[bh] = lse2 * 0.6931471805599453f;
+    }
+  }
+}
+
+// Lengths of the caches with token 0 taken off, for the concentration statistics.
+__global__ __launch_bounds__(256) void sr_rest_lens_kernel(const int32_t* seq_lens, int32_t* rest, int B, int Lmax) {
+  const int b = blockIdx.x * 256 + threadIdx.x;
+  if (b < B) rest[b] = max(clamp_len(seq_lens[b], Lmax) - 1, 0);
+}
+
+}  // namespace
+
+#endif
