@@ -338,6 +338,48 @@ __global__ __launch_bounds__(kThreads, 2) void sr_partial_balanced_kernel(Partia
   if (tid < NG) lens[tid] = clamp_len(len_first, a.Lmax);
   for (int i = tid + kThreads; i < NG; i += kThreads) lens[i] = clamp_len(a.seq_lens[i / a.Hkv], a.Lmax);
   __syncthreads();
+  if (NG <= 64) {
+    // Up to 64 groups: every wavefront builds the whole schedule in registers (lane = group), so no
+    // further barrier or LDS round trip stands between the routing decision and the first K/V load.
+    const bool live = lane < NG;
+    const int len_i = live ? lens[lane] : 0;
+    bool skip = false;
+    float S = 0.f;
+    if (live) {
+      if (kFused) skip = a.rule.routing ? route_decide(cosv + lane * G, G, len_i, a.rule, &S) : false;
+      else skip = a.mask[lane] != 0;
+    }
+    if (kFused && p == 0 && wave == 0 && live) { a.mask[lane] = skip ? 1 : 0; if (a.group_score) a.group_score[lane] = S; }
+    const int u = (live && !skip) ? (len_i + kBlock - 1) / kBlock : 0;
+    int x = u;                                   // inclusive scan over the groups
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int y = __shfl_up(x, o, 64);
+      if (lane >= o) x += y;
+    }
+    const int start_i = x - u;
+    const int U = __builtin_amdgcn_readlane(x, 63);
+    const int c = (U + P - 1) / P;
+    if (p == 0 && wave == 0) {
+      if (lane == 0) { a.sched[0] = U; a.sched[1] = c; a.sched[2 + NG] = U; }
+      if (live) a.sched[2 + lane] = start_i;
+    }
+    const int u_lo = p * c, u_hi = min(u_lo + c, U);
+    if (u_lo >= u_hi) return;
+    const unsigned long long holds = __ballot(u > 0 && start_i <= u_lo && u_lo < start_i + u);   // exactly one group
+    for (int i = __ffsll(holds) - 1; i < NG; ++i) {
+      const int s0 = __builtin_amdgcn_readlane(start_i, i);
+      if (s0 >= u_hi) break;
+      const int un = __builtin_amdgcn_readlane(u, i);
+      if (un == 0) continue;                      // Sink Group or empty sequence
+      const int L = __builtin_amdgcn_readlane(len_i, i);
+      const int b = i / a.Hkv, g = i - b * a.Hkv;
+      const int blk_lo = max(u_lo, s0) - s0, blk_hi = min(u_hi, s0 + un) - s0;
+      attend_range<kPaged>(a, b, g, L, blk_lo * kBlock, min(blk_hi * kBlock, L), p - s0 / c);
+      __syncthreads();                            // LDS of attend_range is reused by the next segment
+    }
+    return;
+  }
   int carry = 0;
   for (int base = 0; base < NG; base += kThreads) {
     const int i = base + tid;
