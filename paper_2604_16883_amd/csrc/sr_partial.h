@@ -294,6 +294,19 @@ __global__ __launch_bounds__(kThreads, 2) void sr_partial_fixed_kernel(PartialAr
 // and anchor rows are a few tens of KB, served by L2), as the paper's kernel does inline, so no
 // separate probe launch precedes it; workgroup 0 writes skip mask and group scores.  Otherwise
 // the mask written by sr_probe_kernel is read.
+// Inclusive prefix sum over the 64 lanes without LDS traffic: shifts inside each row of 16 lanes, then the
+// totals of the rows are carried over with the two row-broadcast moves (lane 15 -> next row, lane 31 ->
+// upper half).  Lanes without a source add 0.
+__device__ __forceinline__ int wave_inclusive_scan(int x) {
+  x += __builtin_amdgcn_update_dpp(0, x, 0x111, 0xF, 0xF, false);   // row_shr:1
+  x += __builtin_amdgcn_update_dpp(0, x, 0x112, 0xF, 0xF, false);   // row_shr:2
+  x += __builtin_amdgcn_update_dpp(0, x, 0x114, 0xF, 0xF, false);   // row_shr:4
+  x += __builtin_amdgcn_update_dpp(0, x, 0x118, 0xF, 0xF, false);   // row_shr:8
+  x += __builtin_amdgcn_update_dpp(0, x, 0x142, 0xA, 0xF, false);   // row_bcast:15 into rows 1 and 3
+  x += __builtin_amdgcn_update_dpp(0, x, 0x143, 0xC, 0xF, false);   // row_bcast:31 into rows 2 and 3
+  return x;
+}
+
 template <bool kFused, bool kPaged>
 __global__ __launch_bounds__(kThreads, 2) void sr_partial_balanced_kernel(PartialArgs a) {
   __shared__ int start[kMaxSchedGroups + 1];
@@ -305,7 +318,8 @@ __global__ __launch_bounds__(kThreads, 2) void sr_partial_balanced_kernel(Partia
   const int NG = a.NG, G = a.G;
   // share index = workgroup index: the stream has no reuse, so which XCD works on which share is
   // immaterial (giving each XCD one contiguous eighth of the blocks measured the same)
-  const int p = blockIdx.x, P = gridDim.x;
+  const int p = blockIdx.x;
+  constexpr int P = kBalancedGrid;               // the host launches exactly this grid
   // the first length load is issued here and parked in a register, so that it and the probe's query /
   // anchor loads are in flight together (one memory round trip at kernel start instead of two)
   int len_first = 0;
@@ -351,12 +365,7 @@ __global__ __launch_bounds__(kThreads, 2) void sr_partial_balanced_kernel(Partia
     }
     if (kFused && p == 0 && wave == 0 && live) { a.mask[lane] = skip ? 1 : 0; if (a.group_score) a.group_score[lane] = S; }
     const int u = (live && !skip) ? (len_i + kBlock - 1) / kBlock : 0;
-    int x = u;                                   // inclusive scan over the groups
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-      const int y = __shfl_up(x, o, 64);
-      if (lane >= o) x += y;
-    }
+    const int x = wave_inclusive_scan(u);        // over the groups
     const int start_i = x - u;
     const int U = __builtin_amdgcn_readlane(x, 63);
     const int c = (U + P - 1) / P;
