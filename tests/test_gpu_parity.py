@@ -68,6 +68,11 @@ def test_large_batches_take_the_unfused_and_fixed_paths():
     sb = synth.generate(w, seq_lens=[300 - 7 * b for b in range(20)])
     reps = _check(sb, label="B20 (unfused probe)")
     assert 0 < reps[0]["skip_ratio"] < 1
+    # more than 512 query heads but at most 64 groups: separate probe kernel + schedule built in registers
+    w = synth.Workload("wide_groups", 40, 16, 1, 260, 0.6, base_seed=95)
+    sb = synth.generate(w, seq_lens=[260 - 6 * b for b in range(40)])
+    reps = _check(sb, label="B40 G16 (unfused probe, 40 groups)")
+    assert 0 < reps[0]["skip_ratio"] < 1
     # exactly 512 query heads: the fused probe sweeps four times
     w = synth.Workload("fused512", 16, 32, 8, 200, 0.6, base_seed=93)
     sb = synth.generate(w, seq_lens=[200 - 11 * (b % 9) for b in range(16)])
