@@ -225,6 +225,12 @@ int decode_impl(const void* q, const void* k, const void* v, const int32_t* seq_
     c.out = static_cast<uint32_t*>(out);
     c.Hq = p->n_q_heads; c.Hkv = p->n_kv_heads; c.G = lay.plan.group_size; c.Lmax = p->max_seq_len;
     c.chunk = lay.plan.chunk_tokens; c.slots = lay.plan.slots_per_head;
+    {   // records per head when every group is active: shares / groups + 1 (balanced), else the chunk count
+      const int NG = p->batch * p->n_kv_heads;
+      const int expect = balanced ? kBalancedGrid / NG + 1 : lay.plan.num_splits;
+      const int rows = (expect + kCombineThreads / 64 - 1) / (kCombineThreads / 64);
+      c.spec = rows < 1 ? 1 : (rows > 8 ? 8 : rows);
+    }
     hipLaunchKernelGGL(sr_combine_kernel, dim3(p->batch * p->n_q_heads), dim3(kCombineThreads), 0, st, c);
     ok = hipGetLastError() == hipSuccess;
   }

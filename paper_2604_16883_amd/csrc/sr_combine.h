@@ -17,6 +17,7 @@ struct CombineArgs {
   const int32_t* sched;   // balanced schedule, else NULL
   uint32_t* out;          // bf16 pairs
   int Hq, Hkv, G, Lmax, chunk, slots;
+  int spec;               // records per wavefront requested before their number is known (1..8)
   // diagnostics (optional): log-sum-exp of the scaled scores and softmax mass on token 0 per head
   const uint32_t* q;      // bf16 pairs
   const void* k;          // contiguous key cache (diagnostics are not offered for paged caches)
@@ -30,12 +31,29 @@ struct CombineArgs {
   float* mean_rest_out;
 };
 
+// One pass: every wavefront keeps a running (max, sum, weighted rows) over the records it owns
+// (record s belongs to wavefront s % 16) and the 16 wavefronts are merged through LDS.  The first
+// records of every wavefront (spec of them) are requested at once at kernel entry, before the number of records
+// is known (it takes a load of the mask and of the schedule to know it), so the merge costs one
+// memory round trip; what was fetched beyond the last record is discarded.  The host sets how many
+// (spec): enough for the records a head has when every group is active, more would be wasted reads.
 __global__ __launch_bounds__(kCombineThreads) void sr_combine_kernel(CombineArgs a) {
   constexpr int NW = kCombineThreads / 64;
   constexpr int UN = 8;
   const int bh = blockIdx.x;
   const int b = bh / a.Hq, h = bh - b * a.Hq, g = h / a.G;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const float2* ml = reinterpret_cast<const float2*>(a.part_ml) + (size_t)bh * a.slots;
+  const float2* po = reinterpret_cast<const float2*>(a.part_o) + (size_t)bh * a.slots * (kD / 2);
+  float2 st[UN], o[UN];
+#pragma unroll
+  for (int u = 0; u < UN; ++u) {                 // slots that do not exist are read as the last one and dropped below
+    if (u < a.spec) {
+      const int s = min(wave + u * NW, a.slots - 1);
+      st[u] = ml[s];
+      o[u] = po[(size_t)s * (kD / 2) + lane];
+    }
+  }
   const int L = clamp_len(a.seq_lens[b], a.Lmax);
   const int bg = b * a.Hkv + g;
   uint32_t* orow = a.out + (size_t)bh * (kD / 2);
@@ -64,49 +82,53 @@ __global__ __launch_bounds__(kCombineThreads) void sr_combine_kernel(CombineArgs
     }
     return;
   }
-  const float2* ml = reinterpret_cast<const float2*>(a.part_ml) + (size_t)bh * a.slots;
-  const float2* po = reinterpret_cast<const float2*>(a.part_o) + (size_t)bh * a.slots * (kD / 2);
-
   __shared__ float red_m[NW];
   __shared__ float red_l[NW];
   __shared__ float2 red_o[NW][64];
-  float mx = -INFINITY;
-  for (int s = threadIdx.x; s < n; s += kCombineThreads) mx = fmaxf(mx, ml[s].x);
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
-  if (lane == 0) red_m[wave] = mx;
-  __syncthreads();
-  float M = red_m[0];
-#pragma unroll
-  for (int u = 1; u < NW; ++u) M = fmaxf(M, red_m[u]);
-
+  float m_run = -INFINITY, lsum = 0.f;
   float2 acc = make_float2(0.f, 0.f);
-  float lsum = 0.f;
   for (int s0 = wave; s0 < n; s0 += NW * UN) {   // UN rows in flight per wavefront
-    float2 st[UN], o[UN];
+    const int have = s0 == wave ? a.spec : 0;    // rows of this batch that are already here
 #pragma unroll
     for (int u = 0; u < UN; ++u) {
-      const int s = s0 + u * NW;
-      const bool ok = s < n;
-      st[u] = ok ? ml[s] : make_float2(-INFINITY, 0.f);
-      o[u] = ok ? po[(size_t)s * (kD / 2) + lane] : make_float2(0.f, 0.f);
+      if (u >= have && s0 + u * NW < n) {
+        const int s = s0 + u * NW;
+        st[u] = ml[s];
+        o[u] = po[(size_t)s * (kD / 2) + lane];
+      }
     }
+    float bm = m_run;
 #pragma unroll
     for (int u = 0; u < UN; ++u) {
-      const float wt = __builtin_amdgcn_exp2f(st[u].x - M);
-      acc.x += wt * o[u].x;
-      acc.y += wt * o[u].y;
+      if (s0 + u * NW >= n) st[u] = make_float2(-INFINITY, 0.f);
+      bm = fmaxf(bm, st[u].x);
+    }
+    const float keep = __builtin_amdgcn_exp2f(m_run - bm);   // bm is finite: row s0 exists
+    acc.x *= keep; acc.y *= keep; lsum *= keep;
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      const bool ok = s0 + u * NW < n;
+      const float wt = __builtin_amdgcn_exp2f(st[u].x - bm);
+      acc.x += ok ? wt * o[u].x : 0.f;
+      acc.y += ok ? wt * o[u].y : 0.f;
       lsum += wt * st[u].y;
     }
+    m_run = bm;
   }
   red_o[wave][lane] = acc;
-  if (lane == 0) red_l[wave] = lsum;
+  if (lane == 0) { red_m[wave] = m_run; red_l[wave] = lsum; }
   __syncthreads();
-  if (wave == 0) {
-    float2 t = red_o[0][lane];
-    float l = red_l[0];
+  float M = red_m[0];                            // wavefront 0 owns record 0, so M is finite
 #pragma unroll
-    for (int u = 1; u < NW; ++u) { t.x += red_o[u][lane].x; t.y += red_o[u][lane].y; l += red_l[u]; }
+  for (int u = 1; u < NW; ++u) M = fmaxf(M, red_m[u]);
+  if (wave == 0) {
+    float2 t = make_float2(0.f, 0.f);
+    float l = 0.f;
+#pragma unroll
+    for (int u = 0; u < NW; ++u) {
+      const float wt = __builtin_amdgcn_exp2f(red_m[u] - M);   // 0 for a wavefront without records
+      t.x += wt * red_o[u][lane].x; t.y += wt * red_o[u][lane].y; l += wt * red_l[u];
+    }
     const float inv = 1.0f / l;
     orow[lane] = f32_to_bf16_rne(t.x * inv) | (f32_to_bf16_rne(t.y * inv) << 16);
     if (a.lse_out || a.alpha0_out) {
