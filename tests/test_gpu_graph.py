@@ -68,3 +68,42 @@ def test_graph_replays_match_eager(paged):
     g.replay()
     torch.cuda.synchronize()
     assert torch.equal(out, ref_out)
+
+
+def test_concurrent_streams_with_distinct_workspaces():
+    """Calls on two streams with their own workspaces and outputs may overlap; each reproduces what
+    it gives alone."""
+    import torch
+    w = synth.WORKLOADS["c1"].scaled(20000, batch=2)
+    sbs = [synth.generate(w, seed=31), synth.generate(w, seed=32)]
+    B, Hq, Hkv, Lmax = w.batch, w.n_q_heads, w.n_kv_heads, sbs[0].max_seq_len
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    ctx = []
+    for sb, st in zip(sbs, streams):
+        p = binding.make_route_params(B, Hq, Hkv, Lmax, stream=st.cuda_stream)
+        plan = binding.sinkrouter_plan(p)
+        ws = torch.empty((plan.workspace_bytes,), dtype=torch.uint8, device="cuda")
+        p.workspace, p.workspace_bytes = ws.data_ptr(), plan.workspace_bytes
+        ctx.append(dict(p=p, ws=ws, q=gu.to_dev(sb.q), k=gu.to_dev(sb.k), v=gu.to_dev(sb.v), sl=gu.to_dev(sb.seq_lens),
+                        out=torch.empty((B, Hq, 128), dtype=torch.int16, device="cuda"),
+                        mask=torch.empty((B, Hkv), dtype=torch.uint8, device="cuda")))
+    torch.cuda.synchronize()
+
+    def call(c):
+        binding.sinkrouter_decode(c["q"], c["k"], c["v"], c["sl"], c["p"], c["out"], c["mask"])
+
+    alone = []
+    for c in ctx:                                 # one after the other
+        call(c)
+        torch.cuda.synchronize()
+        alone.append((c["out"].clone(), c["mask"].clone()))
+        c["out"].fill_(-1)
+        c["mask"].fill_(9)
+    torch.cuda.synchronize()
+    for rep in range(5):                          # interleaved, no synchronisation in between
+        for c in ctx:
+            call(c)
+    torch.cuda.synchronize()
+    for c, (o, m) in zip(ctx, alone):
+        assert torch.equal(c["out"], o) and torch.equal(c["mask"], m)
+    assert not torch.equal(alone[0][0], alone[1][0])
