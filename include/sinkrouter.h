@@ -139,10 +139,14 @@ int sinkrouter_probe(const void* q, const void* k_cache, const int32_t* seq_lens
                      uint8_t* skip_mask_out);
 
 /*
- * sinkrouter_decode with per-kernel timing, for benchmarks: HIP events are recorded on
- * params->stream around each kernel and the call SYNCHRONISES the stream before returning.
- * stage_us (host, 4 floats), in microseconds: separate probe kernel (the gap between two events
- * when the probe is fused into the partial kernel), Split-K partial, merge, total.
+ * sinkrouter_decode with per-kernel timing, for benchmarks.  The call SYNCHRONISES params->stream
+ * before returning.  stage_us (host, 4 floats), in microseconds:
+ *   [0] the separate routing-probe kernel (0 when the probe is fused into the partial kernel),
+ *   [1] the Split-K partial kernel, [2] the merge kernel: each from the begin to the end of the
+ *       kernel's own execution, taken from HIP events attached to the launch (the times a
+ *       profiler's kernel trace shows);
+ *   [3] the whole call, between two events recorded on the stream before the first and after the
+ *       last launch, dispatch latencies included.
  */
 int sinkrouter_decode_profiled(const void* q, const void* k_cache, const void* v_cache,
                                const int32_t* seq_lens, const sr_route_params* params,

@@ -29,6 +29,7 @@
 // sr_common.h, sr_route.h, sr_partial.h, sr_combine.h and sr_measure.h hold the kernels; this file is the
 // host side: argument checks, workspace layout, launches.
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "sinkrouter.h"
@@ -115,8 +116,17 @@ RouteRule make_rule(const sr_route_params* p) {
   return r;
 }
 
+// Plain launch, or (benchmarks) a launch whose own begin and end times are left in two events.
+template <typename Kernel, typename Args>
+bool launch(Kernel kernel, dim3 grid, dim3 block, hipStream_t st, const Args& args, hipEvent_t begin, hipEvent_t end) {
+  if (begin) hipExtLaunchKernelGGL(kernel, grid, block, 0, st, begin, end, 0, args);
+  else hipLaunchKernelGGL(kernel, grid, block, 0, st, args);
+  return hipGetLastError() == hipSuccess;
+}
+
 int launch_probe(const void* q, const void* k, const int32_t* seq_lens, const sr_route_params* p,
-                 const Layout& lay, float* score, uint8_t* mask, hipStream_t st, const PageMap& pm) {
+                 const Layout& lay, float* score, uint8_t* mask, hipStream_t st, const PageMap& pm,
+                 hipEvent_t begin = nullptr, hipEvent_t end = nullptr) {
   ProbeArgs a;
   a.pm = pm;
   a.q = static_cast<const uint4*>(q);
@@ -128,8 +138,7 @@ int launch_probe(const void* q, const void* k, const int32_t* seq_lens, const sr
   a.mask = mask;
   a.Hq = p->n_q_heads; a.Hkv = p->n_kv_heads; a.G = lay.plan.group_size; a.Lmax = p->max_seq_len;
   a.rule = make_rule(p);
-  hipLaunchKernelGGL(sr_probe_kernel, dim3(p->batch * p->n_kv_heads), dim3(64), 0, st, a);
-  return hipGetLastError() == hipSuccess ? SR_OK : SR_ERR_HIP;
+  return launch(sr_probe_kernel, dim3(p->batch * p->n_kv_heads), dim3(64), st, a, begin, end) ? SR_OK : SR_ERR_HIP;
 }
 
 // Outputs of the concentration statistics; decode_impl then attends over tokens 1..L-1 only.
@@ -177,18 +186,19 @@ int decode_impl(const void* q, const void* k, const void* v, const int32_t* seq_
     v = static_cast<const uint16_t*>(v) + kD;
   }
 
-  hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
+  // timing: ev[0] / ev[7] are recorded on the stream around the whole call; ev[1..2], ev[3..4], ev[5..6]
+  // receive the begin and end times of the probe, partial and merge kernels themselves
+  constexpr int kEvents = 8;
+  hipEvent_t ev[kEvents] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
   if (stage_us) {
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < kEvents; ++i)
       if (hipEventCreate(&ev[i]) != hipSuccess) {
         for (int j = 0; j < i; ++j) (void)hipEventDestroy(ev[j]);
         return SR_ERR_HIP;
       }
   }
-  auto mark = [&](int i) { return !stage_us || hipEventRecord(ev[i], st) == hipSuccess; };
-  bool ok = mark(0);
-  if (ok && !fused) ok = launch_probe(q, k_anchor, seq_lens, p, lay, score, mask, st, pm) == SR_OK;
-  if (ok) ok = mark(1);
+  bool ok = !stage_us || hipEventRecord(ev[0], st) == hipSuccess;
+  if (ok && !fused) ok = launch_probe(q, k_anchor, seq_lens, p, lay, score, mask, st, pm, ev[1], ev[2]) == SR_OK;
   if (ok) {
     PartialArgs a;
     a.q = static_cast<const uint16_t*>(q);
@@ -203,16 +213,15 @@ int decode_impl(const void* q, const void* k, const void* v, const int32_t* seq_
     a.scale_log2 = scale * 1.4426950408889634f;
     a.pm = pm;
     const dim3 blk(kThreads), fixed_grid(lay.plan.num_splits, a.NG);
-    if (fused && paged)       hipLaunchKernelGGL((sr_partial_balanced_kernel<true, true>), dim3(kBalancedGrid), blk, 0, st, a);
-    else if (fused)           hipLaunchKernelGGL((sr_partial_balanced_kernel<true, false>), dim3(kBalancedGrid), blk, 0, st, a);
-    else if (balanced && paged) hipLaunchKernelGGL((sr_partial_balanced_kernel<false, true>), dim3(kBalancedGrid), blk, 0, st, a);
-    else if (balanced)        hipLaunchKernelGGL((sr_partial_balanced_kernel<false, false>), dim3(kBalancedGrid), blk, 0, st, a);
-    else if (paged)           hipLaunchKernelGGL(sr_partial_fixed_kernel<true>, fixed_grid, blk, 0, st, a);
-    else                      hipLaunchKernelGGL(sr_partial_fixed_kernel<false>, fixed_grid, blk, 0, st, a);
-    ok = hipGetLastError() == hipSuccess;
+    const dim3 grid = balanced ? dim3(kBalancedGrid) : fixed_grid;
+    if (fused && paged)       ok = launch(sr_partial_balanced_kernel<true, true>, grid, blk, st, a, ev[3], ev[4]);
+    else if (fused)           ok = launch(sr_partial_balanced_kernel<true, false>, grid, blk, st, a, ev[3], ev[4]);
+    else if (balanced && paged) ok = launch(sr_partial_balanced_kernel<false, true>, grid, blk, st, a, ev[3], ev[4]);
+    else if (balanced)        ok = launch(sr_partial_balanced_kernel<false, false>, grid, blk, st, a, ev[3], ev[4]);
+    else if (paged)           ok = launch(sr_partial_fixed_kernel<true>, grid, blk, st, a, ev[3], ev[4]);
+    else                      ok = launch(sr_partial_fixed_kernel<false>, grid, blk, st, a, ev[3], ev[4]);
   }
   const float scale_log2 = (p->sm_scale > 0.f ? p->sm_scale : 0.08838834764831845f) * 1.4426950408889634f;
-  if (ok) ok = mark(2);
   if (ok) {
     CombineArgs c;
     c.q = static_cast<const uint32_t*>(q); c.k = k_anchor;
@@ -231,23 +240,23 @@ int decode_impl(const void* q, const void* k, const void* v, const int32_t* seq_
       const int rows = (expect + kCombineThreads / 64 - 1) / (kCombineThreads / 64);
       c.spec = rows < 1 ? 1 : (rows > 8 ? 8 : rows);
     }
-    hipLaunchKernelGGL(sr_combine_kernel, dim3(p->batch * p->n_q_heads), dim3(kCombineThreads), 0, st, c);
-    ok = hipGetLastError() == hipSuccess;
+    ok = launch(sr_combine_kernel, dim3(p->batch * p->n_q_heads), dim3(kCombineThreads), st, c, ev[5], ev[6]);
   }
-  if (ok) ok = mark(3);
   if (stage_us) {
-    if (ok) ok = hipEventSynchronize(ev[3]) == hipSuccess;
-    if (ok) {
-      for (int i = 0; i < 3 && ok; ++i) {
-        float ms = 0.f;
-        ok = hipEventElapsedTime(&ms, ev[i], ev[i + 1]) == hipSuccess;
-        stage_us[i] = ms * 1000.f;
-      }
+    if (ok) ok = hipEventRecord(ev[7], st) == hipSuccess;
+    if (ok) ok = hipEventSynchronize(ev[7]) == hipSuccess;
+    auto span_us = [&](int i, int j, float* us) {
       float ms = 0.f;
-      if (ok) ok = hipEventElapsedTime(&ms, ev[0], ev[3]) == hipSuccess;
-      stage_us[3] = ms * 1000.f;
-    }
-    for (int i = 0; i < 4; ++i) (void)hipEventDestroy(ev[i]);
+      if (hipEventElapsedTime(&ms, ev[i], ev[j]) != hipSuccess) return false;
+      *us = ms * 1000.f;
+      return true;
+    };
+    stage_us[0] = 0.f;
+    if (ok && !fused) ok = span_us(1, 2, &stage_us[0]);
+    if (ok) ok = span_us(3, 4, &stage_us[1]);
+    if (ok) ok = span_us(5, 6, &stage_us[2]);
+    if (ok) ok = span_us(0, 7, &stage_us[3]);
+    for (int i = 0; i < kEvents; ++i) (void)hipEventDestroy(ev[i]);
   }
   return ok ? SR_OK : SR_ERR_HIP;
 }
