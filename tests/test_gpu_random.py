@@ -51,3 +51,29 @@ def test_random_case(case):
         vp, _ = synth.to_pages(sb.v, sb.seq_lens, pt, seed=case)
         pres = run_paged(sb, kp, vp, tab, pt, **kw)
         assert np.array_equal(pres["out_bits"], res["out_bits"]) and np.array_equal(pres["mask"], res["mask"])
+
+
+N_WIDE = int(os.environ.get("SR_RANDOM_WIDE_CASES", "24"))
+
+
+@pytest.mark.parametrize("case", range(N_WIDE))
+def test_random_wide_batches(case):
+    """Larger batches: both sides of the 512-head limit of the fused probe and of the 64-group limit of
+    the register-built schedule, short ragged sequences."""
+    rng = np.random.default_rng(20_000 + case)
+    Hq, Hkv = [(16, 1), (32, 8), (8, 8), (12, 2), (64, 8), (4, 1)][case % 6]
+    B = int(rng.choice([3, 9, 17, 33, 48, 70]))
+    Lmax = int(rng.choice([64, 130, 257, 400]))
+    sl = [int(rng.integers(0, Lmax + 1)) for _ in range(B)]
+    sl[int(rng.integers(0, B))] = Lmax
+    w = synth.Workload("wide_rnd", B, Hq, Hkv, Lmax, float(rng.uniform(0.3, 0.8)), base_seed=500 + case, planted_per_head=4)
+    sb = synth.generate(w, seed=500 + case, seq_lens=sl)
+    tau = float(np.float32(rng.uniform(0.3, 0.7)))
+    kw = dict(tau_coef=(0, 0, 0, tau))
+    if case % 5 == 4:
+        kw["num_splits"] = int(rng.integers(1, 4))
+    okw = {k: v for k, v in kw.items() if k != "num_splits"}
+    ref = oracle.decode(sb.q, sb.k, sb.v, sb.seq_lens, want_dense=True, **okw)
+    res = gu.run_hip(sb.q, sb.k, sb.v, sb.seq_lens, **kw)
+    rep = gu.compare(res, ref, w.group_size, "wide case %d" % case)
+    print("wide", case, dict(B=B, Hq=Hq, Hkv=Hkv, Lmax=Lmax, heads=B * Hq, groups=B * Hkv, **kw), rep, flush=True)
