@@ -438,7 +438,95 @@ def check_concentration(lib=None):
     assert np.all(np.isnan(a0[1])) and np.all(np.isnan(mx[1])) and np.all(np.isnan(mean[1])) and np.all(rest[1] == 0.0)
 
 
+def check_length_clamp(lib=None):
+    """Lengths outside [0, L_max] are clamped before anything uses them: a negative length behaves as 0
+    (zero output, mask 0, lse -inf, tau evaluated at x = 0), one beyond the stride as the stride.  The
+    threshold is length-dependent here, so a clamp applied to the attention but not to tau shows."""
+    B, Hq, Hkv, D, L = 4, 4, 2, 8, 6
+    q, k, v, _ = synth.random_small(1000, B, Hq, Hkv, D, L)
+    qf, kf = synth.bf16_bits_to_f32(q), synth.bf16_bits_to_f32(k)
+    for b in range(B):                       # group 0 of every sequence points along its anchor: S = 1
+        qf[b, :2] = kf[b, 0, 0]
+    q = synth.f32_to_bf16_bits(qf)
+    coef, norm = (0.0, 0.0, 0.25, 0.5), 6.0          # tau(x) = 0.25 x + 0.5, x = L / 6
+    sl = [-3, 0, L + 9, L]
+    r = oracle.decode(q, k, v, sl, tau_coef=coef, len_norm=norm, want_dense=True, libpath=lib)
+    np.testing.assert_allclose(r.tau, [0.5, 0.5, 0.75, 0.75], rtol=0, atol=1e-15)
+    for b in (0, 1):                         # no valid row: nothing to attend over, never a Sink Group
+        assert np.all(r.out[b] == 0.0) and np.all(r.dense_out[b] == 0.0)
+        assert r.mask[b].tolist() == [0, 0]
+        assert np.all(np.isneginf(r.lse[b]))
+    ref, lse, _ = library_attention(q, k, v, [0, 0, L, L])
+    assert r.mask[2].tolist() == [1, 0] and r.mask[3].tolist() == [1, 0]
+    np.testing.assert_allclose(r.dense_out, ref, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(r.lse[2:], lse[2:], rtol=1e-12, atol=1e-13)
+    assert np.all(r.out[2:, :2] == 0.0)
+    np.testing.assert_allclose(r.out[2:, 2:], ref[2:, 2:], rtol=1e-12, atol=1e-13)
+    # the same through the route-only and the Split-K entries
+    rr = oracle.route(q, k, sl, tau_coef=coef, len_norm=norm, libpath=lib)
+    np.testing.assert_allclose(rr.tau, [0.5, 0.5, 0.75, 0.75], rtol=0, atol=1e-15)
+    np.testing.assert_array_equal(rr.mask, r.mask)
+    o2, m2, pm, pl = oracle.decode_splitk(q, k, v, sl, [0, 4, L + 20], tau_coef=coef, len_norm=norm, libpath=lib)
+    np.testing.assert_array_equal(m2, r.mask)
+    np.testing.assert_allclose(o2, r.out, rtol=1e-12, atol=1e-13)
+    assert np.all(np.isneginf(pm[:2])) and np.all(pl[:2] == 0.0)
+    # concentration statistics and the page gather clamp the same way
+    a0, mx, mean, rest = oracle.concentration(q, k, v, sl, libpath=lib)
+    assert np.all(np.isnan(a0[:2])) and np.all(rest[:2] == 0.0)
+    np.testing.assert_array_equal(a0[2], oracle.concentration(q[2:3], k[2:3], v[2:3], [L], libpath=lib)[0][0])
+    kp, tab = synth.to_pages(k, [0, 0, L, L], 2, seed=3)
+    got = oracle.gather_pages(kp, tab, sl, L, libpath=lib)
+    assert np.all(got[:2] == 0) and np.array_equal(got[2:], k[2:])
+
+
+def check_nan_norms(lib=None):
+    """A cosine whose denominator is not a positive number is 0 (zero or NaN norm alike): a NaN in a
+    query, or in the anchor when its norm is recomputed, makes that head's cosine exactly 0, and the
+    group mean is the mean of the remaining cosines.  With a finite cached norm and a NaN anchor the
+    denominator is fine, the dot product is NaN, the score is NaN, and the strict comparison keeps the
+    group active whatever the threshold."""
+    D = 8
+    k0 = np.array([1.0, 0, 0, 0, 0, 0, 0, 0])
+    qs = np.stack([3.0 * k0, 0.5 * k0, -2.0 * k0, k0])              # cosines 1, 1, -1, 1
+    q = bits(qs[None])                                               # one group of r = 4, and ...
+    q = np.concatenate([q, q], axis=1)                               # ... a second group with the same heads
+    k = bits(np.tile(k0, (1, 2, 3, 1)))
+    v = bits(np.ones((1, 2, 3, D)))
+    base = oracle.decode(q, k, v, [3], tau_coef=(0, 0, 0, 0.4), want_dense=True, libpath=lib)
+    np.testing.assert_array_equal(base.head_cos[0], [1, 1, -1, 1, 1, 1, -1, 1])
+    np.testing.assert_array_equal(base.group_score[0], [0.5, 0.5])
+    assert base.mask[0].tolist() == [1, 1]
+    nan = np.uint16(0x7FC0)
+    qn = q.copy()
+    qn[0, 1, 5] = nan                                                # NaN in one query of group 0
+    r = oracle.decode(qn, k, v, [3], tau_coef=(0, 0, 0, 0.4), want_dense=True, libpath=lib)
+    assert r.head_cos[0, 1] == 0.0 and not np.signbit(r.head_cos[0, 1])
+    np.testing.assert_array_equal(r.head_cos[0], [1, 0, -1, 1, 1, 1, -1, 1])
+    np.testing.assert_array_equal(r.group_score[0], [0.25, 0.5])
+    assert r.mask[0].tolist() == [0, 1]                              # 0.25 < 0.4 < 0.5
+    kn = k.copy()
+    kn[0, 1, 0, 2] = nan                                             # NaN in the anchor of group 1, norm recomputed
+    r = oracle.decode(q, kn, v, [3], tau_coef=(0, 0, 0, -0.5), want_dense=True, libpath=lib)
+    np.testing.assert_array_equal(r.head_cos[0], [1, 1, -1, 1, 0, 0, 0, 0])
+    np.testing.assert_array_equal(r.group_score[0], [0.5, 0.0])
+    assert r.mask[0].tolist() == [1, 1]                              # S = 0 > -0.5: the zero cosines do count
+    r = oracle.route(q, kn, [3], tau_coef=(0, 0, 0, 0.0), libpath=lib)
+    assert r.mask[0].tolist() == [1, 0]                              # 0 > 0 is false
+    # the same anchor kept apart from the cache
+    r = oracle.route(q, k, [3], tau_coef=(0, 0, 0, -0.5), k0=kn[:, :, 0].copy(), libpath=lib)
+    np.testing.assert_array_equal(r.group_score[0], [0.5, 0.0])
+    # finite cached norm, NaN anchor: NaN score, group active even at tau = -2
+    r = oracle.route(q, kn, [3], tau_coef=(0, 0, 0, -2.0), k0_norm=np.ones((1, 2)), libpath=lib)
+    assert np.isnan(r.group_score[0, 1]) and r.group_score[0, 0] == 0.5
+    assert r.mask[0].tolist() == [1, 0]
+    # a cached norm that is negative or NaN counts as "not cached": the norm is recomputed from the anchor
+    for bad in (np.nan, -1.0):
+        r = oracle.route(q, k, [3], tau_coef=(0, 0, 0, 0.4), k0_norm=np.array([[2.0, bad]]), libpath=lib)
+        np.testing.assert_array_equal(r.group_score[0], [0.25, 0.5])
+        assert r.mask[0].tolist() == [0, 1]
+
+
 ALL_PINS = [check_golden, check_brute_force_dense, check_routed_vs_library,
             check_splitk_equals_single_pass, check_closed_forms, check_cosine_properties,
             check_decision_properties, check_skip_error_bound, check_symmetries, check_separate_anchor, check_paged_gather,
-            check_concentration]
+            check_concentration, check_length_clamp, check_nan_norms]

@@ -10,12 +10,13 @@ from paper_2604_16883_amd import binding, synth
 import gpu_util as gu
 
 
-def run_paged(sb, kp, vp, table, page_tokens, **kw):
+def run_paged(sb, kp, vp, table, page_tokens, given_lens=None, **kw):
     import torch
     w = sb.workload
     B, Hq, Hkv = w.batch, w.n_q_heads, w.n_kv_heads
     Lmax = sb.max_seq_len
-    dev = dict(q=gu.to_dev(sb.q), k=gu.to_dev(kp), v=gu.to_dev(vp), sl=gu.to_dev(sb.seq_lens), t=gu.to_dev(table))
+    dev = dict(q=gu.to_dev(sb.q), k=gu.to_dev(kp), v=gu.to_dev(vp), sl=gu.to_dev(np.asarray(sb.seq_lens if given_lens is None else given_lens, np.int32)),
+               t=gu.to_dev(table))
     p = binding.make_route_params(B, Hq, Hkv, Lmax, **kw)
     plan = binding.sinkrouter_plan(p)
     ws = torch.empty((plan.workspace_bytes,), dtype=torch.uint8, device="cuda")

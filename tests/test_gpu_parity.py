@@ -114,6 +114,52 @@ def test_edge_lengths():
         assert np.array_equal(res["out_bits"][1, h], sb.v[1, h // 4, 0])
 
 
+def test_lengths_outside_the_cache_are_clamped_on_the_device():
+    """seq_lens below 0 or above the cache stride: the device clamps them to [0, L_max] before the
+    threshold, the schedule and the attention use them.  The caches hold NaN patterns wherever the
+    clamped length says no valid row is, the threshold depends on the length (so a clamp that missed
+    tau would flip decisions: unclamped, the huge lengths give tau far below -1), and every path that
+    reads a length is taken: fused probe + balanced schedule, fixed chunks + separate probe, paged."""
+    from test_gpu_paged import run_paged
+    Lmax = 300
+    given = [-5, 0, Lmax + 17, Lmax, 131, -2 ** 31, 2 ** 31 - 1, 1]
+    valid = [0, 0, Lmax, Lmax, 131, 0, Lmax, 1]
+    w = synth.Workload("clamp", len(given), 8, 2, Lmax, 0.5, base_seed=78)
+    sb = synth.generate(w, seq_lens=valid, max_seq_len=Lmax)
+    kw = dict(tau_coef=(0.0, 0.0, -0.3, 0.85), len_norm=float(Lmax))          # tau(L_max) = 0.55
+    ref = oracle.decode(sb.q, sb.k, sb.v, given, want_dense=True, **kw)
+    same = oracle.decode(sb.q, sb.k, sb.v, valid, want_dense=True, **kw)
+    assert np.array_equal(ref.mask, same.mask) and np.array_equal(ref.out, same.out) and np.array_equal(ref.tau, same.tau)
+    assert 0 < ref.mask.mean() < 1
+    results = []
+    for extra in (dict(), dict(num_splits=3), dict(routing_enabled=False)):
+        print("clamp", extra, flush=True)
+        r = ref if extra.get("routing_enabled", True) else oracle.decode(sb.q, sb.k, sb.v, given, want_dense=True,
+                                                                         routing_enabled=False, **kw)
+        res = gu.run_hip(sb.q, sb.k, sb.v, given, **kw, **extra)
+        rep = gu.compare(res, r, w.group_size, "clamp %s" % extra)
+        print("clamp", extra, rep, flush=True)
+        for b in (0, 1, 5):
+            assert np.all(res["out_bits"][b] == 0) and not res["mask"][b].any()
+        results.append(res)
+    kp, table = synth.to_pages(sb.k, valid, 64, seed=5)
+    vp, _ = synth.to_pages(sb.v, valid, 64, seed=5)
+    for extra, cont in ((dict(), results[0]), (dict(num_splits=3), results[1])):
+        print("clamp paged", extra, flush=True)
+        pres = run_paged(sb, kp, vp, table, 64, given_lens=given, **kw, **extra)
+        assert np.array_equal(pres["out_bits"], cont["out_bits"]) and np.array_equal(pres["mask"], cont["mask"])
+    # a wide batch (more than 512 query heads): the separate probe kernel and the LDS-built schedule
+    B = 70
+    given = [(-7, 0, 200 + 9, 200, 77, 2 ** 31 - 1, -2 ** 31)[b % 7] for b in range(B)]
+    valid = [min(max(x, 0), 200) for x in given]
+    w = synth.Workload("clamp_wide", B, 8, 2, 200, 0.5, base_seed=79, planted_per_head=4)
+    sb = synth.generate(w, seq_lens=valid, max_seq_len=200)
+    kw = dict(tau_coef=(0.0, 0.0, -0.3, 0.85), len_norm=200.0)
+    ref = oracle.decode(sb.q, sb.k, sb.v, given, want_dense=True, **kw)
+    res = gu.run_hip(sb.q, sb.k, sb.v, given, **kw)
+    print("clamp wide", gu.compare(res, ref, w.group_size, "clamp wide"), flush=True)
+
+
 def test_threshold_cubic_scale_and_cached_norm():
     w = synth.WORKLOADS["c1"].scaled(900, batch=3)
     sb = synth.generate(w, seed=5, seq_lens=[900, 450, 200])

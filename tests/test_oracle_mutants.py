@@ -52,6 +52,11 @@ MUTANTS = [
     ("concentration_not_normalised", "for (int32_t t = 0; t < L; ++t) w[t] /= total;", ""),
     ("concentration_rest_not_renormalised", "for (int d = 0; d < D; ++d) orow[d] /= rest;", ""),
     ("concentration_scale_dropped", "w[t] = s * scale;", "w[t] = s;"),
+    ("negative_length_not_clamped", "if (L < 0) return 0;", ""),
+    ("overlong_length_not_clamped_for_tau", "int32_t L = clamp_len(seq_lens[b], c->max_seq_len);\n    double tau = tau_of(c, L);",
+     "int32_t L = clamp_len(seq_lens[b], c->max_seq_len);\n    double tau = tau_of(c, seq_lens[b]);"),
+    ("nan_denominator_not_zeroed", "if (!(den > 0.0)) return 0.0;", "if (den == 0.0) return 0.0;"),
+    ("nan_cached_norm_used", "nk = anchor_norm >= 0.0 ? anchor_norm : sqrt(nk);", "nk = !(anchor_norm < 0.0) ? anchor_norm : sqrt(nk);"),
     ("separate_anchor_wrong_group", "k0_rows + ((size_t)b * Hkv + g) * D", "k0_rows + ((size_t)b * Hkv) * D"),
 ]
 
@@ -74,6 +79,6 @@ def test_mutant_is_caught(name, old, new, source, tmp_path):
     for pin in oracle_pins.ALL_PINS:
         try:
             pin(str(so))
-        except AssertionError:
+        except (AssertionError, RuntimeError):      # a pin fails, or the broken oracle itself reports an error
             caught.append(pin.__name__)
     assert caught, "no pin notices the planted mistake '%s'" % name
