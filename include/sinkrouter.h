@@ -51,7 +51,9 @@ typedef enum sr_status {
  * tau(x) = a x^3 + b x^2 + c x + d of Appendix A evaluated at x = seq_lens[b] / len_norm.
  * The paper prints neither the coefficients nor the normalisation, so both are inputs; a
  * fixed threshold t is {0,0,0,t} (the paper's operating point is 0.55).  K_0 is row 0 of the
- * group's key cache.  A zero norm gives cosine 0; a NaN score leaves the group active.
+ * group's key cache.  A cosine whose denominator is not a positive number (a zero or NaN norm) is
+ * 0; a NaN score (NaN anchor with a finite cached norm) leaves the group active.  A cached norm
+ * that is negative or NaN counts as not cached and is recomputed from the anchor.
  */
 typedef struct sr_route_params {
   uint32_t struct_size;     /* sizeof(sr_route_params); anything else -> SR_ERR_UNSUPPORTED */
@@ -113,7 +115,10 @@ size_t sinkrouter_workspace_bytes(const sr_route_params* params /*host*/);
  *   v_cache       device bf16 [B,H_kv,L_max,D]
  *   seq_lens      device int32 [B]: valid rows per sequence, current token included;
  *                 values outside [0,L_max] are clamped on the device.  Rows at or beyond
- *                 seq_lens[b] are never read.
+ *                 seq_lens[b] are never read, with one exception: row 0 of every (sequence,
+ *                 KV group) key cache is always read by the routing probe (unless params->k0
+ *                 supplies the anchors), also for an empty sequence, whose result is then
+ *                 discarded; the caches must therefore hold at least one row.
  *   params        host
  *   out           device bf16 [B,H_q,D]: softmax(scale q K^T) V for heads of Active Groups
  *                 (fp32 accumulation, rounded to nearest even), exact zeros for heads of
@@ -202,7 +207,9 @@ typedef struct sr_paged_layout {
  * gathering the pages would give.
  *   k_pages, v_pages device bf16 [n_pages,H_kv,page_tokens,D]
  *   block_table      device int32 [B,pages_per_seq]: physical page of each logical page; only
- *                    entries below ceil(seq_lens[b] / page_tokens) are read
+ *                    entries below ceil(seq_lens[b] / page_tokens) are read, and entry 0 of
+ *                    every sequence (the anchor's page; for an empty sequence any value will
+ *                    do, it is clamped to the pool like every entry)
  * params->max_seq_len bounds the sequence lengths (they are clamped to it); params->k0 and
  * params->k0_norm work as for the contiguous entry point.  Token 0 is the first token of the
  * page block_table[b][0].

@@ -26,14 +26,16 @@
 //   sr_combine_kernel  log-sum-exp merge of the partials, bf16 output; zeros for Sink Groups
 //                      (Eq. 14).
 //
-// sr_common.h, sr_route.h, sr_partial.h, sr_combine.h and sr_measure.h hold the kernels; this file is the
-// host side: argument checks, workspace layout, launches.
+// sr_common.h, sr_route.h, sr_partial.h, sr_combine.h and sr_measure.h hold the kernels, sr_config.h the
+// constants and index arithmetic host and device share, sr_host.h the argument checks, launch plan and
+// workspace layout (plain C++, no GPU needed); this file launches.
 #include <hip/hip_runtime.h>
 #include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "sinkrouter.h"
 
+#include "sr_host.h"
 #include "sr_common.h"
 #include "sr_route.h"
 #include "sr_partial.h"
@@ -43,79 +45,8 @@
 namespace {
 
 // ------------------------------------------------------------------------------------------
-// Host side.
+// Host side: launches.  Argument checks, plan and workspace layout are in sr_host.h.
 // ------------------------------------------------------------------------------------------
-inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
-
-struct Layout {
-  sr_plan plan;
-  size_t off_o, off_ml, off_score, off_sched, off_lens;
-};
-
-int make_layout(const sr_route_params* p, Layout* lay) {
-  if (!p) return SR_ERR_NULL;
-  if (p->struct_size != sizeof(sr_route_params)) return SR_ERR_UNSUPPORTED;
-  if (p->batch < 1 || p->n_q_heads < 1 || p->n_kv_heads < 1 || p->max_seq_len < 1 || p->num_splits < 0)
-    return SR_ERR_SHAPE;
-  if (p->n_q_heads % p->n_kv_heads != 0) return SR_ERR_SHAPE;
-  if ((int64_t)p->batch * p->n_kv_heads > 65535) return SR_ERR_SHAPE;
-  if ((int64_t)p->batch * p->n_q_heads > (int64_t)1 << 24) return SR_ERR_SHAPE;
-  if (p->max_seq_len > (1 << 24)) return SR_ERR_SHAPE;          // 32-bit token arithmetic stays exact
-  if (p->head_dim != kD || p->kv_block != kBlock) return SR_ERR_UNSUPPORTED;
-  const int G = p->n_q_heads / p->n_kv_heads;
-  if (G > kMaxGroup) return SR_ERR_UNSUPPORTED;
-  if (!(p->sm_scale >= 0.f) || p->sm_scale > 1e30f) return SR_ERR_SHAPE;
-
-  const int NG = p->batch * p->n_kv_heads;
-  const int blocks = (p->max_seq_len + kBlock - 1) / kBlock;
-  sr_plan& pl = lay->plan;
-  pl.group_size = G;
-  if (p->num_splits == 0 && NG <= kMaxSchedGroups && (int64_t)NG * blocks < ((int64_t)1 << 30)) {
-    pl.schedule = 1;
-    pl.chunk_tokens = 0;
-    pl.num_splits = 0;
-    pl.partial_grid = kBalancedGrid;
-    pl.slots_per_head = blocks < kBalancedGrid + 1 ? blocks : kBalancedGrid + 1;
-  } else {
-    int chunk;
-    if (p->num_splits > 0) {
-      const int per = (p->max_seq_len + p->num_splits - 1) / p->num_splits;
-      chunk = (int)align_up((size_t)per, kChunkUnit);
-    } else {
-      // too many groups to schedule in LDS: plain chunks sized so that, with about 40% of the
-      // groups active (the paper's retained budget, Section 5.1), some 2048 workgroups have work
-      const double active_tokens = 0.4 * (double)NG * p->max_seq_len;
-      int units = (int)(active_tokens / (2048.0 * kChunkUnit));
-      units = units < 1 ? 1 : (units > 8 ? 8 : units);
-      chunk = units * kChunkUnit;
-    }
-    pl.schedule = 0;
-    pl.chunk_tokens = chunk;
-    pl.num_splits = (p->max_seq_len + chunk - 1) / chunk;
-    pl.partial_grid = pl.num_splits * NG;
-    pl.slots_per_head = pl.num_splits;
-  }
-  const size_t heads = (size_t)p->batch * p->n_q_heads;
-  const size_t S = (size_t)pl.slots_per_head;
-  lay->off_o = 0;
-  lay->off_ml = align_up(heads * S * kD * sizeof(float), 256);
-  lay->off_score = lay->off_ml + align_up(heads * S * 2 * sizeof(float), 256);
-  lay->off_sched = lay->off_score + align_up((size_t)NG * sizeof(float), 256);
-  lay->off_lens = lay->off_sched + align_up((size_t)(NG + 3) * sizeof(int32_t), 256);
-  pl.workspace_bytes = lay->off_lens + align_up((size_t)p->batch * sizeof(int32_t), 256);
-  return SR_OK;
-}
-
-inline bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
-
-RouteRule make_rule(const sr_route_params* p) {
-  RouteRule r;
-  for (int i = 0; i < 4; ++i) r.tau[i] = p->tau_coef[i];
-  r.len_norm = p->len_norm;
-  r.routing = p->routing_enabled != 0;
-  return r;
-}
-
 // Plain launch, or (benchmarks) a launch whose own begin and end times are left in two events.
 template <typename Kernel, typename Args>
 bool launch(Kernel kernel, dim3 grid, dim3 block, hipStream_t st, const Args& args, hipEvent_t begin, hipEvent_t end) {
@@ -150,19 +81,13 @@ struct RestStats {
 int decode_impl(const void* q, const void* k, const void* v, const int32_t* seq_lens,
                 const sr_route_params* p, void* out, uint8_t* mask, float* stage_us,
                 float* lse_out = nullptr, float* alpha0_out = nullptr, const PageMap* pages = nullptr,
-                const RestStats* rest = nullptr) {
-  if (!q || !k || !v || !seq_lens || !p || !out || !mask) return SR_ERR_NULL;
+                const RestStats* rest = nullptr, void* own_workspace = nullptr) {
   Layout lay;
-  int rc = make_layout(p, &lay);
+  const DecodeExtras extras = {lse_out, alpha0_out, rest ? rest->max_rest : nullptr, rest ? rest->mean_rest : nullptr};
+  const int rc = check_decode_args(q, k, v, seq_lens, p, out, mask, extras, own_workspace == nullptr, &lay);
   if (rc != SR_OK) return rc;
-  if (misaligned(q, 16) || misaligned(k, 16) || misaligned(v, 16) || misaligned(out, 16) || misaligned(seq_lens, 4) ||
-      misaligned(p->k0, 16) || misaligned(p->k0_norm, 4) || misaligned(lse_out, 4) || misaligned(alpha0_out, 4) ||
-      (rest && (misaligned(rest->max_rest, 4) || misaligned(rest->mean_rest, 4))))
-    return SR_ERR_ALIGN;
-  if (!p->workspace || misaligned(p->workspace, 256) || p->workspace_bytes < lay.plan.workspace_bytes)
-    return SR_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(p->stream);
-  char* ws = static_cast<char*>(p->workspace);
+  char* ws = static_cast<char*>(own_workspace ? own_workspace : p->workspace);
   float* part_o = reinterpret_cast<float*>(ws + lay.off_o);
   float* part_ml = reinterpret_cast<float*>(ws + lay.off_ml);
   float* score = reinterpret_cast<float*>(ws + lay.off_score);
@@ -209,8 +134,7 @@ int decode_impl(const void* q, const void* k, const void* v, const int32_t* seq_
     a.Hq = p->n_q_heads; a.Hkv = p->n_kv_heads; a.G = lay.plan.group_size; a.Lmax = p->max_seq_len;
     a.NG = p->batch * p->n_kv_heads;
     a.chunk = lay.plan.chunk_tokens; a.slots = lay.plan.slots_per_head;
-    const float scale = p->sm_scale > 0.f ? p->sm_scale : 0.08838834764831845f;   // 1/sqrt(128)
-    a.scale_log2 = scale * 1.4426950408889634f;
+    a.scale_log2 = scale_log2_of(p);
     a.pm = pm;
     const dim3 blk(kThreads), fixed_grid(lay.plan.num_splits, a.NG);
     const dim3 grid = balanced ? dim3(kBalancedGrid) : fixed_grid;
@@ -221,11 +145,10 @@ int decode_impl(const void* q, const void* k, const void* v, const int32_t* seq_
     else if (paged)           ok = launch(sr_partial_fixed_kernel<true>, grid, blk, st, a, ev[3], ev[4]);
     else                      ok = launch(sr_partial_fixed_kernel<false>, grid, blk, st, a, ev[3], ev[4]);
   }
-  const float scale_log2 = (p->sm_scale > 0.f ? p->sm_scale : 0.08838834764831845f) * 1.4426950408889634f;
   if (ok) {
     CombineArgs c;
     c.q = static_cast<const uint32_t*>(q); c.k = k_anchor;
-    c.lse_out = lse_out; c.alpha0_out = alpha0_out; c.scale_log2 = scale_log2;
+    c.lse_out = lse_out; c.alpha0_out = alpha0_out; c.scale_log2 = scale_log2_of(p);
     c.lens_full = lens_full;
     c.max_rest_out = rest ? rest->max_rest : nullptr;
     c.mean_rest_out = rest ? rest->mean_rest : nullptr;
@@ -234,12 +157,7 @@ int decode_impl(const void* q, const void* k, const void* v, const int32_t* seq_
     c.out = static_cast<uint32_t*>(out);
     c.Hq = p->n_q_heads; c.Hkv = p->n_kv_heads; c.G = lay.plan.group_size; c.Lmax = p->max_seq_len;
     c.chunk = lay.plan.chunk_tokens; c.slots = lay.plan.slots_per_head;
-    {   // records per head when every group is active: shares / groups + 1 (balanced), else the chunk count
-      const int NG = p->batch * p->n_kv_heads;
-      const int expect = balanced ? kBalancedGrid / NG + 1 : lay.plan.num_splits;
-      const int rows = (expect + kCombineThreads / 64 - 1) / (kCombineThreads / 64);
-      c.spec = rows < 1 ? 1 : (rows > 8 ? 8 : rows);
-    }
+    c.spec = combine_spec_rows(lay, p->batch * p->n_kv_heads);
     ok = launch(sr_combine_kernel, dim3(p->batch * p->n_q_heads), dim3(kCombineThreads), st, c, ev[5], ev[6]);
   }
   if (stage_us) {
@@ -330,18 +248,9 @@ int sinkrouter_concentration(const void* q, const void* k_cache, const void* v_c
 int sinkrouter_decode_paged(const void* q, const void* k_pages, const void* v_pages, const int32_t* block_table,
                             const int32_t* seq_lens, const sr_route_params* params, const sr_paged_layout* layout,
                             void* out, uint8_t* skip_mask_out) {
-  if (!block_table || !layout || !params) return SR_ERR_NULL;
-  if (layout->struct_size != sizeof(sr_paged_layout)) return SR_ERR_UNSUPPORTED;
-  const int pt = layout->page_tokens;
-  if (pt < kBlock || (pt & (pt - 1)) != 0) return SR_ERR_UNSUPPORTED;       // power of two, >= one block
-  if (layout->n_pages < 1 || layout->pages_per_seq < 1) return SR_ERR_SHAPE;
-  if (params->max_seq_len < 1 || (int64_t)layout->pages_per_seq * pt < params->max_seq_len) return SR_ERR_SHAPE;
-  if (misaligned(block_table, 4)) return SR_ERR_ALIGN;
   PageMap pm;
-  pm.table = block_table;
-  pm.page_shift = __builtin_ctz((unsigned)pt);
-  pm.pages_per_seq = layout->pages_per_seq;
-  pm.n_pages = layout->n_pages;
+  const int rc = check_paged_args(block_table, layout, params, &pm);
+  if (rc != SR_OK) return rc;
   return decode_impl(q, k_pages, v_pages, seq_lens, params, out, skip_mask_out, nullptr, nullptr, nullptr, &pm);
 }
 

@@ -5,29 +5,15 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "sr_config.h"
+
 #ifndef SR_P_SPLIT
 #define SR_P_SPLIT 1      // softmax weights enter the P.V MFMA as bf16 hi + bf16 lo (1) or bf16 only (0)
 #endif
 
 namespace {
 
-constexpr int kD = 128;              // head dimension
-constexpr int kBlock = 64;           // tokens per online-softmax block (B_K)
-#ifndef SR_WAVES
-#define SR_WAVES 4
-#endif
-constexpr int kWaves = SR_WAVES;     // wavefronts per partial workgroup
-constexpr int kThreads = 64 * kWaves;
-constexpr int kMaxGroup = 16;        // query heads per KV group that fit the MFMA tile
-constexpr int kChunkUnit = kBlock * kWaves;
 constexpr int kOStride = kD + 4;     // LDS row stride (floats) of the per-wave output tile
-constexpr int kCombineThreads = 1024;
-#ifndef SR_GRID
-#define SR_GRID 256
-#endif
-constexpr int kBalancedGrid = SR_GRID;   // one workgroup per compute unit: measured best (512 and 1024 are 3-6% slower)
-constexpr int kMaxSchedGroups = 2048;  // (sequence, KV group) pairs the balanced schedule scans in LDS
-constexpr int kMaxFusedHeads = 512;    // query heads (all sequences) the balanced kernel probes itself
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -48,27 +34,6 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
   if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0u;
   u += 0x7fffu + ((u >> 16) & 1u);
   return u >> 16;
-}
-
-__device__ __forceinline__ int clamp_len(int L, int Lmax) { return L < 0 ? 0 : (L > Lmax ? Lmax : L); }
-
-// Paged KV cache: pages of 2^page_shift tokens laid out [n_pages, H_kv, page_tokens, D]; logical
-// page j of sequence b is physical page table[b * pages_per_seq + j] (clamped to the pool, so a
-// bad entry reads a wrong page but never leaves the allocation).  table == NULL: contiguous cache.
-struct PageMap {
-  const int32_t* table;
-  int page_shift, pages_per_seq, n_pages;
-};
-
-__device__ __forceinline__ int page_of(const PageMap& pm, int b, int tok) {
-  int pg = pm.table[(size_t)b * pm.pages_per_seq + (tok >> pm.page_shift)];
-  pg = pg < 0 ? 0 : pg;
-  return pg < pm.n_pages ? pg : pm.n_pages - 1;
-}
-
-// Offset (in 16-byte units) of token `tok` of group g in a page pool, given its physical page.
-__device__ __forceinline__ size_t paged_offset(const PageMap& pm, int page, int Hkv, int g, int tok) {
-  return ((((size_t)page * Hkv + g) << pm.page_shift) + (tok & ((1 << pm.page_shift) - 1))) * (kD / 8);
 }
 
 // K_0 of (sequence, KV group) bg: row bg of the separately cached anchors [B,H_kv,D] when the caller

@@ -1,0 +1,69 @@
+// SinkRouter decode attention for MI355X: compile-time constants and the pure index arithmetic that host and
+// device share (length clamp, page addressing, the routing rule's parameters).  Nothing here needs the HIP
+// runtime, so the host side of the library (sr_host.h) and its CPU tests build with a plain C++ compiler.
+#ifndef SR_CONFIG_H
+#define SR_CONFIG_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#if defined(__HIPCC__)
+#define SR_HD __host__ __device__ __forceinline__
+#else
+#define SR_HD inline
+#endif
+
+#ifndef SR_WAVES
+#define SR_WAVES 4
+#endif
+#ifndef SR_GRID
+#define SR_GRID 256
+#endif
+
+namespace {
+
+constexpr int kD = 128;              // head dimension
+constexpr int kBlock = 64;           // tokens per online-softmax block (B_K)
+constexpr int kWaves = SR_WAVES;     // wavefronts per partial workgroup
+constexpr int kThreads = 64 * kWaves;
+constexpr int kMaxGroup = 16;        // query heads per KV group that fit the MFMA tile
+constexpr int kChunkUnit = kBlock * kWaves;
+constexpr int kCombineThreads = 1024;
+constexpr int kBalancedGrid = SR_GRID;   // persistent workgroups of the balanced schedule: one per compute unit
+constexpr int kMaxSchedGroups = 2048;  // (sequence, KV group) pairs the balanced schedule scans in LDS
+constexpr int kMaxFusedHeads = 512;    // query heads (all sequences) the balanced kernel probes itself
+constexpr int kMaxGroupsTotal = 65535; // (sequence, KV group) pairs per call: the y extent of the fixed grid
+constexpr int kMaxSeqLen = 1 << 24;    // 32-bit token arithmetic stays exact up to here
+constexpr int64_t kMaxHeadsTotal = (int64_t)1 << 24;
+
+// seq_lens[b] as the kernels use it: values outside [0, L_max] are clamped.
+SR_HD int clamp_len(int L, int Lmax) { return L < 0 ? 0 : (L > Lmax ? Lmax : L); }
+
+// Paged KV cache: pages of 2^page_shift tokens laid out [n_pages, H_kv, page_tokens, D]; logical
+// page j of sequence b is physical page table[b * pages_per_seq + j] (clamped to the pool, so a
+// bad entry reads a wrong page but never leaves the allocation).  table == NULL: contiguous cache.
+struct PageMap {
+  const int32_t* table;
+  int page_shift, pages_per_seq, n_pages;
+};
+
+SR_HD int page_of(const PageMap& pm, int b, int tok) {
+  int pg = pm.table[(size_t)b * pm.pages_per_seq + (tok >> pm.page_shift)];
+  pg = pg < 0 ? 0 : pg;
+  return pg < pm.n_pages ? pg : pm.n_pages - 1;
+}
+
+// Offset (in 16-byte units) of token `tok` of group g in a page pool, given its physical page.
+SR_HD size_t paged_offset(const PageMap& pm, int page, int Hkv, int g, int tok) {
+  return ((((size_t)page * Hkv + g) << pm.page_shift) + (tok & ((1 << pm.page_shift) - 1))) * (kD / 8);
+}
+
+// Parameters of the routing rule (Section 4.2, Appendix A) as the kernels receive them.
+struct RouteRule {
+  float tau[4], len_norm;
+  int routing;
+};
+
+}  // namespace
+
+#endif

@@ -13,11 +13,6 @@ namespace {
 // the probe fused into the balanced partial kernel run exactly this arithmetic, in this order, so
 // their decisions are identical.
 // ------------------------------------------------------------------------------------------
-struct RouteRule {
-  float tau[4], len_norm;
-  int routing;
-};
-
 // x + x of the lane whose index differs in bit 0 (kXor1) or bit 1 of the quad: one DPP move each.
 template <int kCtrl>
 __device__ __forceinline__ float quad_swap_add(float x) {

@@ -153,6 +153,17 @@ def test_alignment_and_workspace_errors():
     assert lib.sinkrouter_hbm_read_probe((1 << 16) + 4, 1024, 1 << 17, None) == B.SR_ERR_ALIGN
 
 
+def test_plan_rejects_a_fixed_grid_beyond_32_bits():
+    # 65536 chunks of 256 tokens x 65535 groups: the workgroup count does not fit a 32-bit grid
+    p = B.make_route_params(65535, 1, 1, 1 << 24, num_splits=65536)
+    with pytest.raises(B.SinkRouterError) as e:
+        B.sinkrouter_plan(p)
+    assert e.value.status == B.SR_ERR_SHAPE
+    assert B.sinkrouter_workspace_bytes(p) == 0
+    pl = B.sinkrouter_plan(B.make_route_params(32767, 1, 1, 1 << 24, num_splits=65536))
+    assert pl.partial_grid == 65536 * 32767 and pl.num_splits == 65536
+
+
 def test_paged_argument_errors():
     p = B.make_route_params(1, 32, 8, 4096, workspace=0x70000, workspace_bytes=1 << 30)
     args = (0x10000, 0x20000, 0x30000, 0x80000, 0x40000)
