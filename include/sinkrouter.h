@@ -11,7 +11,8 @@
  * Conventions for every entry point
  *   - "device" pointers are HIP device memory on the current device, "host" pointers
  *     are ordinary host memory.  The caller owns every buffer; the library allocates
- *     no device memory and keeps no state between calls.
+ *     no device memory and keeps no state between calls (sinkrouter_decode_static alone
+ *     works on a device array that belongs to the library, see there).
  *   - bf16 tensors are raw 16-bit patterns, row-major, innermost dimension D, and must
  *     be 16-byte aligned.
  *   - Calls are asynchronous on params->stream and never synchronise (except the
@@ -39,7 +40,8 @@ typedef enum sr_status {
   SR_ERR_UNSUPPORTED = -3, /* head_dim != 128, group size > 16, kv_block != 64, bad struct_size */
   SR_ERR_WORKSPACE = -4,   /* workspace missing, misaligned or smaller than required */
   SR_ERR_ALIGN = -5,       /* a tensor pointer is not 16-byte aligned */
-  SR_ERR_HIP = -6          /* the HIP runtime reported an error (launch, event, ...) */
+  SR_ERR_HIP = -6,         /* the HIP runtime reported an error (launch, event, ...) */
+  SR_ERR_STATIC_LIMIT = -7 /* sinkrouter_decode_static: the shape needs more than the static scratch */
 } sr_status;
 
 /*
@@ -218,6 +220,25 @@ int sinkrouter_decode_paged(const void* q, const void* k_pages, const void* v_pa
                             const int32_t* block_table, const int32_t* seq_lens,
                             const sr_route_params* params, const sr_paged_layout* layout,
                             void* out, uint8_t* skip_mask_out);
+
+/*
+ * sinkrouter_decode for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, kernels, schedule and result (bit for bit) as sinkrouter_decode, except that
+ * params->workspace and params->workspace_bytes are ignored: the partial records live in a device
+ * array of SINKROUTER_STATIC_SCRATCH_BYTES that is part of the library's code object (every GPU
+ * the library runs on holds it until the process ends).  The call allocates and frees nothing; the
+ * array's address is looked up on the first call on each device.  A shape whose
+ * sinkrouter_plan().workspace_bytes exceeds SINKROUTER_STATIC_SCRATCH_BYTES returns
+ * SR_ERR_STATIC_LIMIT (checked on the host, before any HIP call); all five benchmark shapes fit.
+ * Nothing in the array has to start at zero (every record is written before it is read), so
+ * nothing is cleared.  All calls on one GPU share the array: calls that overlap on one GPU (other
+ * streams, other threads) race; calls on one stream are ordered and safe.
+ */
+#define SINKROUTER_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
+int sinkrouter_decode_static(const void* q, const void* k_cache, const void* v_cache,
+                             const int32_t* seq_lens, const sr_route_params* params,
+                             void* out, uint8_t* skip_mask_out);
 
 /*
  * Prefill-side anchor caching (Section 4.1): copies row 0 of every (sequence, KV group) key cache

@@ -23,6 +23,8 @@ SR_ERR_UNSUPPORTED = -3
 SR_ERR_WORKSPACE = -4
 SR_ERR_ALIGN = -5
 SR_ERR_HIP = -6
+SR_ERR_STATIC_LIMIT = -7
+STATIC_SCRATCH_BYTES = 32 << 20
 
 
 class RouteParams(ctypes.Structure):
@@ -97,6 +99,8 @@ def load() -> ctypes.CDLL:
         lib.sinkrouter_workspace_bytes.restype = ctypes.c_size_t
         lib.sinkrouter_decode.argtypes = [vp, vp, vp, i32p, pp, vp, vp]
         lib.sinkrouter_decode.restype = ctypes.c_int
+        lib.sinkrouter_decode_static.argtypes = [vp, vp, vp, i32p, pp, vp, vp]
+        lib.sinkrouter_decode_static.restype = ctypes.c_int
         lib.sinkrouter_decode_profiled.argtypes = [vp, vp, vp, i32p, pp, vp, vp, ctypes.POINTER(ctypes.c_float)]
         lib.sinkrouter_decode_profiled.restype = ctypes.c_int
         lib.sinkrouter_decode_diag.argtypes = [vp, vp, vp, i32p, pp, vp, vp, vp, vp]
@@ -202,6 +206,17 @@ def sinkrouter_decode(q, k_cache, v_cache, seq_lens, route_params: RouteParams, 
                                   ctypes.byref(p), _addr(out), _addr(skip_mask_out))
     if check and rc != SR_OK:
         raise SinkRouterError(rc, "sinkrouter_decode")
+    return rc
+
+
+def sinkrouter_decode_static(q, k_cache, v_cache, seq_lens, route_params: RouteParams, out, skip_mask_out,
+                             check: bool = True) -> int:
+    """sinkrouter_decode on the library's own static scratch: no workspace, nothing allocated."""
+    p = _with_stream(route_params)
+    rc = load().sinkrouter_decode_static(_addr(q), _addr(k_cache), _addr(v_cache), _addr(seq_lens),
+                                         ctypes.byref(p), _addr(out), _addr(skip_mask_out))
+    if check and rc != SR_OK:
+        raise SinkRouterError(rc, "sinkrouter_decode_static")
     return rc
 
 

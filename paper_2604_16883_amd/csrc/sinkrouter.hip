@@ -33,6 +33,8 @@
 #include <hip/hip_ext.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "sinkrouter.h"
 
 #include "sr_host.h"
@@ -41,6 +43,13 @@
 #include "sr_partial.h"
 #include "sr_combine.h"
 #include "sr_measure.h"
+
+static_assert(kStaticScratchBytes == SINKROUTER_STATIC_SCRATCH_BYTES, "header and kernels disagree on the static scratch size");
+
+// Scratch of the allocation-free entry point (sinkrouter_decode_static): the workspace of one decode call,
+// held by every GPU the library runs on until the process ends.  In host code this name is only a handle
+// for hipGetSymbolAddress; kernels receive the device address looked up once per device.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace {
 
@@ -70,6 +79,25 @@ int launch_probe(const void* q, const void* k, const int32_t* seq_lens, const sr
   a.Hq = p->n_q_heads; a.Hkv = p->n_kv_heads; a.G = lay.plan.group_size; a.Lmax = p->max_seq_len;
   a.rule = make_rule(p);
   return launch(sr_probe_kernel, dim3(p->batch * p->n_kv_heads), dim3(64), st, a, begin, end) ? SR_OK : SR_ERR_HIP;
+}
+
+// Device address of `scratch` on the current device, looked up on the first call per device (each GPU
+// holds its own copy of the array at its own address).  No allocation: the array is part of the
+// library's code object.
+bool static_scratch(void** ptr) {
+  constexpr int kMaxDevices = 64;
+  static void* addr[kMaxDevices] = {};
+  static std::mutex guard;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return false;
+  std::lock_guard<std::mutex> lock(guard);
+  if (!addr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return false;
+    addr[dev] = p;
+  }
+  *ptr = addr[dev];
+  return true;
 }
 
 // Outputs of the concentration statistics; decode_impl then attends over tokens 1..L-1 only.
@@ -254,6 +282,20 @@ int sinkrouter_decode_paged(const void* q, const void* k_pages, const void* v_pa
   return decode_impl(q, k_pages, v_pages, seq_lens, params, out, skip_mask_out, nullptr, nullptr, nullptr, &pm);
 }
 
+int sinkrouter_decode_static(const void* q, const void* k_cache, const void* v_cache, const int32_t* seq_lens,
+                             const sr_route_params* params, void* out, uint8_t* skip_mask_out) {
+  // every host-side check first, the size limit included, so that error paths touch no GPU
+  Layout lay;
+  const DecodeExtras none = {nullptr, nullptr, nullptr, nullptr};
+  const int rc = check_decode_args(q, k_cache, v_cache, seq_lens, params, out, skip_mask_out, none, false, &lay);
+  if (rc != SR_OK) return rc;
+  if (lay.plan.workspace_bytes > kStaticScratchBytes) return SR_ERR_STATIC_LIMIT;
+  void* ws = nullptr;
+  if (!static_scratch(&ws)) return SR_ERR_HIP;
+  return decode_impl(q, k_cache, v_cache, seq_lens, params, out, skip_mask_out, nullptr, nullptr, nullptr, nullptr,
+                     nullptr, ws);
+}
+
 int sinkrouter_extract_anchor(const void* k_cache, const sr_route_params* params, void* k0_out, float* k0_norm_out) {
   if (!k_cache || !params || (!k0_out && !k0_norm_out)) return SR_ERR_NULL;
   Layout lay;
@@ -294,6 +336,7 @@ const char* sinkrouter_status_string(int status) {
     case SR_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case SR_ERR_ALIGN: return "tensor pointer not 16-byte aligned";
     case SR_ERR_HIP: return "HIP runtime error";
+    case SR_ERR_STATIC_LIMIT: return "shape needs more workspace than the library's static scratch holds (SINKROUTER_STATIC_SCRATCH_BYTES): use sinkrouter_decode with a caller workspace";
     default: return "unknown status";
   }
 }

@@ -35,6 +35,8 @@ constexpr int kMaxFusedHeads = 512;    // query heads (all sequences) the balanc
 constexpr int kMaxGroupsTotal = 65535; // (sequence, KV group) pairs per call: the y extent of the fixed grid
 constexpr int kMaxSeqLen = 1 << 24;    // 32-bit token arithmetic stays exact up to here
 constexpr int64_t kMaxHeadsTotal = (int64_t)1 << 24;
+// The allocation-free entry point keeps its partial records in a device array of this size.
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
 
 // seq_lens[b] as the kernels use it: values outside [0, L_max] are clamped.
 SR_HD int clamp_len(int L, int Lmax) { return L < 0 ? 0 : (L > Lmax ? Lmax : L); }

@@ -188,6 +188,14 @@ int main() {
   cur = shape(0, 0, 0, 0, 0);
   Layout lay;
   CHECK(make_layout(nullptr, &lay) == SR_ERR_NULL);
+  // static scratch: the five benchmark shapes fit, a 512-head batch at 32K does not
+  const int bench[][4] = {{1, 32, 8, 4096}, {4, 32, 8, 32768}, {1, 32, 4, 200000}, {1, 64, 8, 524288}, {2, 40, 40, 65536}};
+  for (auto& b : bench) {
+    const sr_route_params p = shape(b[0], b[1], b[2], b[3], 0);
+    cur = p;
+    CHECK(make_layout(&p, &lay) == SR_OK && lay.plan.workspace_bytes <= kStaticScratchBytes);
+  }
+  { const sr_route_params p = shape(16, 32, 8, 32768, 0); cur = p; CHECK(make_layout(&p, &lay) == SR_OK && lay.plan.workspace_bytes > kStaticScratchBytes); }
   check_pages();
   printf("ok %lld\n", n);
   return 0;

@@ -22,7 +22,7 @@ def declared_functions():
 def test_library_exports_every_declared_symbol():
     lib = B.load()
     names = declared_functions()
-    assert len(names) >= 11
+    assert len(names) >= 12 and "sinkrouter_decode_static" in names
     for n in names:
         assert hasattr(lib, n), "libsinkrouter.so does not export %s" % n
     assert B.sinkrouter_abi_version() == 2
@@ -47,11 +47,12 @@ def test_binding_mirrors_header_structs():
 
 def test_status_strings():
     seen = set()
-    for code in (B.SR_OK, B.SR_ERR_NULL, B.SR_ERR_SHAPE, B.SR_ERR_UNSUPPORTED, B.SR_ERR_WORKSPACE, B.SR_ERR_ALIGN, B.SR_ERR_HIP):
+    for code in (B.SR_OK, B.SR_ERR_NULL, B.SR_ERR_SHAPE, B.SR_ERR_UNSUPPORTED, B.SR_ERR_WORKSPACE, B.SR_ERR_ALIGN, B.SR_ERR_HIP,
+                 B.SR_ERR_STATIC_LIMIT):
         s = B.sinkrouter_status_string(code)
         assert s and s != "unknown status"
         seen.add(s)
-    assert len(seen) == 7
+    assert len(seen) == 8
     assert B.sinkrouter_status_string(-99) == "unknown status"
 
 
@@ -162,6 +163,25 @@ def test_plan_rejects_a_fixed_grid_beyond_32_bits():
     assert B.sinkrouter_workspace_bytes(p) == 0
     pl = B.sinkrouter_plan(B.make_route_params(32767, 1, 1, 1 << 24, num_splits=65536))
     assert pl.partial_grid == 65536 * 32767 and pl.num_splits == 65536
+
+
+def test_static_entry_point_checks_arguments_and_its_size_limit_on_the_host():
+    """sinkrouter_decode_static takes no workspace; every check, the size limit included, precedes any HIP call."""
+    args = (FAKE["q"], FAKE["k"], FAKE["v"], FAKE["sl"])
+    ok = B.make_route_params(1, 32, 8, 4096)                         # no workspace given: fine here
+    assert B.sinkrouter_plan(ok).workspace_bytes <= B.STATIC_SCRATCH_BYTES
+    assert B.sinkrouter_decode_static(None, *args[1:], ok, FAKE["out"], FAKE["mask"], check=False) == B.SR_ERR_NULL
+    assert B.sinkrouter_decode_static(FAKE["q"] + 8, *args[1:], ok, FAKE["out"], FAKE["mask"], check=False) == B.SR_ERR_ALIGN
+    bad = B.make_route_params(1, 32, 8, 4096, head_dim=64)
+    assert B.sinkrouter_decode_static(*args, bad, FAKE["out"], FAKE["mask"], check=False) == B.SR_ERR_UNSUPPORTED
+    for name, (b, hq, hkv, L) in WORKLOAD_SHAPES.items():            # the five benchmark shapes fit
+        assert B.sinkrouter_plan(B.make_route_params(b, hq, hkv, L)).workspace_bytes <= B.STATIC_SCRATCH_BYTES, name
+    big = B.make_route_params(16, 32, 8, 32768)                      # 512 heads x 257 records: 68 MB
+    assert B.sinkrouter_plan(big).workspace_bytes > B.STATIC_SCRATCH_BYTES
+    assert B.sinkrouter_decode_static(*args, big, FAKE["out"], FAKE["mask"], check=False) == B.SR_ERR_STATIC_LIMIT
+    assert "static scratch" in B.sinkrouter_status_string(B.SR_ERR_STATIC_LIMIT)
+    text = open(HEADER).read()
+    assert int(re.search(r"SINKROUTER_STATIC_SCRATCH_BYTES \(\(size_t\)(\d+) << 20\)", text).group(1)) << 20 == B.STATIC_SCRATCH_BYTES
 
 
 def test_paged_argument_errors():
