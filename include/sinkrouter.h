@@ -260,6 +260,13 @@ int sinkrouter_extract_anchor(const void* k_cache, const sr_route_params* params
 int sinkrouter_hbm_read_probe(const void* buf, size_t bytes, void* sink, void* stream);
 int sinkrouter_hbm_copy_probe(void* dst, const void* src, size_t bytes, void* stream);
 
+/*
+ * 0 in the product build.  The measurement variant of the library (built with -DSR_TIMELINE=1, used
+ * only by the benchmark's per-phase accounting) appends this many bytes of per-workgroup wall-clock
+ * stamps to the workspace, already included in sinkrouter_workspace_bytes().
+ */
+size_t sinkrouter_timeline_bytes(void);
+
 /* Static, human-readable text for a status code. */
 const char* sinkrouter_status_string(int status);
 

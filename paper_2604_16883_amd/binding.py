@@ -117,6 +117,8 @@ def load() -> ctypes.CDLL:
         lib.sinkrouter_hbm_read_probe.restype = ctypes.c_int
         lib.sinkrouter_hbm_copy_probe.argtypes = [vp, vp, ctypes.c_size_t, vp]
         lib.sinkrouter_hbm_copy_probe.restype = ctypes.c_int
+        lib.sinkrouter_timeline_bytes.argtypes = []
+        lib.sinkrouter_timeline_bytes.restype = ctypes.c_size_t
         lib.sinkrouter_status_string.argtypes = [ctypes.c_int]
         lib.sinkrouter_status_string.restype = ctypes.c_char_p
         lib.sinkrouter_abi_version.argtypes = []
@@ -171,6 +173,10 @@ def make_route_params(batch: int, n_q_heads: int, n_kv_heads: int, max_seq_len: 
 
 def sinkrouter_status_string(status: int) -> str:
     return load().sinkrouter_status_string(int(status)).decode()
+
+
+def sinkrouter_timeline_bytes() -> int:
+    return int(load().sinkrouter_timeline_bytes())
 
 
 def sinkrouter_abi_version() -> int:

@@ -10,6 +10,8 @@ ROOT = os.path.dirname(HERE)
 SRC = os.path.join(HERE, "csrc", "sinkrouter.hip")
 INCLUDE = os.path.join(ROOT, "include")
 LIB = os.path.join(HERE, "libsinkrouter.so")
+# measurement variant (wall-clock stamps per workgroup, -DSR_TIMELINE=1); only bench.py --timeline loads it
+TIMELINE_LIB = os.path.join(HERE, "libsinkrouter_timeline.so")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -21,8 +23,10 @@ HIPCC_FLAGS = [
 ]
 
 
-def build_library(verbose: bool = False, extra=()) -> str:
-    """Compile the library unconditionally; returns its path."""
+def build_library(verbose: bool = False, extra=(), timeline: bool = False) -> str:
+    """Compile the library (or, with ``timeline``, its measurement variant) unconditionally; returns its path."""
+    LIB = TIMELINE_LIB if timeline else globals()["LIB"]
+    extra = list(extra) + (["-DSR_TIMELINE=1"] if timeline else [])
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     tmp = LIB + ".tmp.%d" % os.getpid()
     cmd = [hipcc] + HIPCC_FLAGS + list(extra) + ["-I", INCLUDE, SRC, "-o", tmp]
@@ -77,4 +81,6 @@ def kernel_resource_usage(log: str) -> dict:
 
 
 if __name__ == "__main__":
-    print(build_library(verbose=True, extra=sys.argv[1:]))
+    args = sys.argv[1:]
+    tl = "--timeline" in args
+    print(build_library(verbose=True, extra=[a for a in args if a != "--timeline"], timeline=tl))

@@ -164,6 +164,7 @@ int decode_impl(const void* q, const void* k, const void* v, const int32_t* seq_
     a.chunk = lay.plan.chunk_tokens; a.slots = lay.plan.slots_per_head;
     a.scale_log2 = scale_log2_of(p);
     a.pm = pm;
+    a.timeline = (SR_TIMELINE && balanced) ? reinterpret_cast<long long*>(ws + lay.off_timeline) : nullptr;
     const dim3 blk(kThreads), fixed_grid(lay.plan.num_splits, a.NG);
     const dim3 grid = balanced ? dim3(kBalancedGrid) : fixed_grid;
     if (fused && paged)       ok = launch(sr_partial_balanced_kernel<true, true>, grid, blk, st, a, ev[3], ev[4]);
@@ -185,6 +186,7 @@ int decode_impl(const void* q, const void* k, const void* v, const int32_t* seq_
     c.out = static_cast<uint32_t*>(out);
     c.Hq = p->n_q_heads; c.Hkv = p->n_kv_heads; c.G = lay.plan.group_size; c.Lmax = p->max_seq_len;
     c.chunk = lay.plan.chunk_tokens; c.slots = lay.plan.slots_per_head;
+    c.timeline = SR_TIMELINE ? reinterpret_cast<long long*>(ws + lay.off_timeline) + (size_t)kBalancedGrid * kTimelinePartialStamps : nullptr;
     c.spec = combine_spec_rows(lay, p->batch * p->n_kv_heads);
     ok = launch(sr_combine_kernel, dim3(p->batch * p->n_q_heads), dim3(kCombineThreads), st, c, ev[5], ev[6]);
   }
@@ -342,5 +344,8 @@ const char* sinkrouter_status_string(int status) {
 }
 
 int sinkrouter_abi_version(void) { return SINKROUTER_ABI_VERSION; }
+
+// Timeline (measurement) build only: bytes of wall-clock stamps at the end of the workspace, 0 in the product build.
+size_t sinkrouter_timeline_bytes(void) { return kTimelineBytes; }
 
 }  // extern "C"

@@ -17,7 +17,7 @@ struct CombineArgs {
   const int32_t* sched;   // balanced schedule, else NULL
   uint32_t* out;          // bf16 pairs
   int Hq, Hkv, G, Lmax, chunk, slots;
-  int spec;               // records per wavefront requested before their number is known (1..8)
+  int spec;               // records per wavefront requested before their number is known (1..kCombineRows)
   // diagnostics (optional): log-sum-exp of the scaled scores and softmax mass on token 0 per head
   const uint32_t* q;      // bf16 pairs
   const void* k;          // contiguous key cache (diagnostics are not offered for paged caches)
@@ -29,18 +29,24 @@ struct CombineArgs {
   const int32_t* lens_full;
   float* max_rest_out;
   float* mean_rest_out;
+  long long* timeline;    // timeline build: [heads, 4] stamps (entry, records loaded, merged, exit); NULL otherwise
 };
 
 // One pass: every wavefront keeps a running (max, sum, weighted rows) over the records it owns
-// (record s belongs to wavefront s % 16) and the 16 wavefronts are merged through LDS.  The first
-// records of every wavefront (spec of them) are requested at once at kernel entry, before the number of records
-// is known (it takes a load of the mask and of the schedule to know it), so the merge costs one
-// memory round trip; what was fetched beyond the last record is discarded.  The host sets how many
-// (spec): enough for the records a head has when every group is active, more would be wasted reads.
+// (record s belongs to wavefront s % 16) and the 16 wavefronts are merged through LDS.  A wavefront
+// holds kCombineRows records in flight (16 measured 1 us slower per step than 8, 2 and 4 the same as 8).
+// The first records of every wavefront (spec of them) are requested at kernel entry, before the number
+// of records is known (it takes a load of the mask and of the schedule to know it); when spec covers the
+// head's records the merge costs one memory round trip.  What was fetched beyond the last record is
+// discarded.  The host sets spec (combine_spec_rows): more would be wasted reads.
 __global__ __launch_bounds__(kCombineThreads) void sr_combine_kernel(CombineArgs a) {
   constexpr int NW = kCombineThreads / 64;
-  constexpr int UN = 8;
+  constexpr int UN = kCombineRows;
   const int bh = blockIdx.x;
+#if SR_TIMELINE
+  long long* tl = (a.timeline && bh < kTimelineMergeGroups) ? a.timeline : nullptr;
+#endif
+  SR_STAMP(tl, kTimelineMergeStamps, 0);
   const int b = bh / a.Hq, h = bh - b * a.Hq, g = h / a.G;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const float2* ml = reinterpret_cast<const float2*>(a.part_ml) + (size_t)bh * a.slots;
@@ -80,6 +86,7 @@ __global__ __launch_bounds__(kCombineThreads) void sr_combine_kernel(CombineArgs
         if (a.alpha0_out) a.alpha0_out[bh] = nan;
       }
     }
+    SR_STAMP(tl, kTimelineMergeStamps, 3);
     return;
   }
   __shared__ float red_m[NW];
@@ -115,9 +122,11 @@ __global__ __launch_bounds__(kCombineThreads) void sr_combine_kernel(CombineArgs
     }
     m_run = bm;
   }
+  SR_STAMP(tl, kTimelineMergeStamps, 1);
   red_o[wave][lane] = acc;
   if (lane == 0) { red_m[wave] = m_run; red_l[wave] = lsum; }
   __syncthreads();
+  SR_STAMP(tl, kTimelineMergeStamps, 2);
   float M = red_m[0];                            // wavefront 0 owns record 0, so M is finite
 #pragma unroll
   for (int u = 1; u < NW; ++u) M = fmaxf(M, red_m[u]);
@@ -155,6 +164,7 @@ __global__ __launch_bounds__(kCombineThreads) void sr_combine_kernel(CombineArgs
       if (a.lse_out && lane == 0) a.lse_out[bh] = lse2 * 0.6931471805599453f;
     }
   }
+  SR_STAMP(tl, kTimelineMergeStamps, 3);
 }
 
 // Lengths of the caches with token 0 taken off, for the concentration statistics.

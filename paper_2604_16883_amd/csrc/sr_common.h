@@ -15,6 +15,13 @@ namespace {
 
 constexpr int kOStride = kD + 4;     // LDS row stride (floats) of the per-wave output tile
 
+// Timeline build: thread 0 of the workgroup stores the chip-wide wall clock into slot i of its row.
+#if SR_TIMELINE
+#define SR_STAMP(buf, per_group, i) do { if ((buf) && threadIdx.x == 0) (buf)[(size_t)blockIdx.x * (per_group) + (i)] = wall_clock64(); } while (0)
+#else
+#define SR_STAMP(buf, per_group, i) do { } while (0)
+#endif
+
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));

@@ -20,6 +20,13 @@
 #define SR_GRID 256
 #endif
 
+// SR_TIMELINE=1 builds the measurement variant of the library: every workgroup of the balanced partial
+// kernel and of the merge kernel leaves wall-clock stamps (100 MHz counter) behind the workspace, which
+// grows by kTimelineBytes.  The product build (0) contains none of it.
+#ifndef SR_TIMELINE
+#define SR_TIMELINE 0
+#endif
+
 namespace {
 
 constexpr int kD = 128;              // head dimension
@@ -29,6 +36,10 @@ constexpr int kThreads = 64 * kWaves;
 constexpr int kMaxGroup = 16;        // query heads per KV group that fit the MFMA tile
 constexpr int kChunkUnit = kBlock * kWaves;
 constexpr int kCombineThreads = 1024;
+#ifndef SR_COMBINE_ROWS
+#define SR_COMBINE_ROWS 8
+#endif
+constexpr int kCombineRows = SR_COMBINE_ROWS;   // partial records a merge wavefront keeps in flight
 constexpr int kBalancedGrid = SR_GRID;   // persistent workgroups of the balanced schedule: one per compute unit
 constexpr int kMaxSchedGroups = 2048;  // (sequence, KV group) pairs the balanced schedule scans in LDS
 constexpr int kMaxFusedHeads = 512;    // query heads (all sequences) the balanced kernel probes itself
@@ -37,6 +48,11 @@ constexpr int kMaxSeqLen = 1 << 24;    // 32-bit token arithmetic stays exact up
 constexpr int64_t kMaxHeadsTotal = (int64_t)1 << 24;
 // The allocation-free entry point keeps its partial records in a device array of this size.
 constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+
+// Timeline build: 8 stamps per partial workgroup, then 4 per merge workgroup (the first kTimelineMergeGroups).
+constexpr int kTimelinePartialStamps = 8, kTimelineMergeStamps = 4, kTimelineMergeGroups = 1024;
+constexpr size_t kTimelineBytes =
+    SR_TIMELINE ? ((size_t)kBalancedGrid * kTimelinePartialStamps + (size_t)kTimelineMergeGroups * kTimelineMergeStamps) * 8 : 0;
 
 // seq_lens[b] as the kernels use it: values outside [0, L_max] are clamped.
 SR_HD int clamp_len(int L, int Lmax) { return L < 0 ? 0 : (L > Lmax ? Lmax : L); }

@@ -14,10 +14,10 @@ inline bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintp
 
 // Byte offsets of the pieces of the workspace, in this order: partial outputs [heads, slots, D] fp32,
 // partial (m, l) [heads, slots, 2] fp32, group scores [NG] fp32, schedule table U, c, start[0..NG] int32,
-// shifted lengths [B] int32 (concentration statistics only).  Every piece starts on a 256-byte boundary.
+// shifted lengths [B] int32 (concentration statistics only), wall-clock stamps (timeline build only).  Every piece starts on a 256-byte boundary.
 struct Layout {
   sr_plan plan;
-  size_t off_o, off_ml, off_score, off_sched, off_lens;
+  size_t off_o, off_ml, off_score, off_sched, off_lens, off_timeline;
 };
 
 // Shape checks, launch plan and workspace layout for params.  All size products are formed in 64 bits.
@@ -73,7 +73,8 @@ inline int make_layout(const sr_route_params* p, Layout* lay) {
   lay->off_score = lay->off_ml + align_up(heads * S * 2 * sizeof(float), 256);
   lay->off_sched = lay->off_score + align_up((size_t)NG * sizeof(float), 256);
   lay->off_lens = lay->off_sched + align_up((size_t)(NG + 3) * sizeof(int32_t), 256);
-  pl.workspace_bytes = lay->off_lens + align_up((size_t)p->batch * sizeof(int32_t), 256);
+  lay->off_timeline = lay->off_lens + align_up((size_t)p->batch * sizeof(int32_t), 256);
+  pl.workspace_bytes = lay->off_timeline + kTimelineBytes;      // no stamps in the product build
   return SR_OK;
 }
 
@@ -136,11 +137,14 @@ inline int check_paged_args(const int32_t* block_table, const sr_paged_layout* l
 }
 
 // Rows the merge kernel requests per wavefront before it knows how many records a head has: enough for
-// a head when every group is active (shares / groups + 1 records in the balanced schedule).
+// a head when every group is active (shares / groups + 1 records in the balanced schedule).  A larger guess
+// (sized for the paper's retained budget of about 40 % of the groups) measured no faster: every head requests
+// these rows, Sink Groups' heads included.
 inline int combine_spec_rows(const Layout& lay, int NG) {
   const int expect = lay.plan.schedule == 1 ? kBalancedGrid / NG + 1 : lay.plan.num_splits;
-  const int rows = (expect + kCombineThreads / 64 - 1) / (kCombineThreads / 64);
-  return rows < 1 ? 1 : (rows > 8 ? 8 : rows);
+  const int waves = kCombineThreads / 64;
+  const int rows = (expect + waves - 1) / waves;
+  return rows < 1 ? 1 : (rows > kCombineRows ? kCombineRows : rows);
 }
 
 }  // namespace

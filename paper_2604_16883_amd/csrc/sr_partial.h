@@ -35,6 +35,7 @@ struct PartialArgs {
   int slots;        // partial records per head
   float scale_log2; // softmax scale * log2(e)
   PageMap pm;
+  long long* timeline;   // timeline build: [grid, 8] stamps; NULL otherwise
 };
 
 // Loads of one 64-token block whose first row is row0 of the slab at Kbase / Vbase (a contiguous
@@ -228,16 +229,26 @@ __device__ __forceinline__ void attend_range(const PartialArgs& a, int b, int g,
     int next = tok0 + kStep;
     // paged: the page of a block is looked up one iteration before the block is prefetched
     int page_n = (kPaged && next < t_end) ? page_of(a.pm, b, next) : 0;
+#if SR_TIMELINE
+    bool first_step = a.timeline && a.timeline[(size_t)blockIdx.x * kTimelinePartialStamps + 4] == 0;
+#endif
     while (next < t_end) {
       const size_t base = slab_base(page_n);
       const int row0 = slab_row(next), row_last = row0 + (last - next);
       if (kPaged) page_n = page_of(a.pm, b, min(next + kStep, last));
       block_step<true>(w, kr, vr, qb, K4 + base, V4 + base, row0, row_last, tok0, t_end, r16, kg, a.scale_log2);
+#if SR_TIMELINE
+      if (first_step) { SR_STAMP(a.timeline, kTimelinePartialStamps, 4); first_step = false; }
+#endif
       tok0 = next;
       next += kStep;
     }
     block_step<false>(w, kr, vr, qb, K4, V4, 0, 0, tok0, t_end, r16, kg, a.scale_log2);
+#if SR_TIMELINE
+    if (first_step) SR_STAMP(a.timeline, kTimelinePartialStamps, 4);
+#endif
   }
+  SR_STAMP(a.timeline, kTimelinePartialStamps, 5);
 
   // ---- merge the 4 wavefronts through LDS, write one partial per head
   float l_run = w.l_run;
@@ -271,6 +282,7 @@ __device__ __forceinline__ void attend_range(const PartialArgs& a, int b, int g,
     *reinterpret_cast<float4*>(a.part_o + rec * kD + 4 * c4) = o;
     if (c4 == 0) *reinterpret_cast<float2*>(a.part_ml + rec * 2) = make_float2(M, l);
   }
+  SR_STAMP(a.timeline, kTimelinePartialStamps, 6);
 }
 
 // Fixed schedule.  grid = (num_splits, B*H_kv), block = 256.
@@ -322,6 +334,7 @@ __global__ __launch_bounds__(kThreads, 2) void sr_partial_balanced_kernel(Partia
   constexpr int P = kBalancedGrid;               // the host launches exactly this grid
   // the first length load is issued here and parked in a register, so that it and the probe's query /
   // anchor loads are in flight together (one memory round trip at kernel start instead of two)
+  SR_STAMP(a.timeline, kTimelinePartialStamps, 0);
   int len_first = 0;
   if (tid < NG) len_first = a.seq_lens[tid / a.Hkv];
   if (kFused && a.rule.routing) {
@@ -351,7 +364,9 @@ __global__ __launch_bounds__(kThreads, 2) void sr_partial_balanced_kernel(Partia
   }
   if (tid < NG) lens[tid] = clamp_len(len_first, a.Lmax);
   for (int i = tid + kThreads; i < NG; i += kThreads) lens[i] = clamp_len(a.seq_lens[i / a.Hkv], a.Lmax);
+  SR_STAMP(a.timeline, kTimelinePartialStamps, 1);
   __syncthreads();
+  SR_STAMP(a.timeline, kTimelinePartialStamps, 2);
   if (NG <= 64) {
     // Up to 64 groups: every wavefront builds the whole schedule in registers (lane = group), so no
     // further barrier or LDS round trip stands between the routing decision and the first K/V load.
@@ -374,6 +389,7 @@ __global__ __launch_bounds__(kThreads, 2) void sr_partial_balanced_kernel(Partia
       if (live) a.sched[2 + lane] = start_i;
     }
     const int u_lo = p * c, u_hi = min(u_lo + c, U);
+    SR_STAMP(a.timeline, kTimelinePartialStamps, 3);
     if (u_lo >= u_hi) return;
     const unsigned long long holds = __ballot(u > 0 && start_i <= u_lo && u_lo < start_i + u);   // exactly one group
     for (int i = __ffsll(holds) - 1; i < NG; ++i) {
@@ -387,6 +403,7 @@ __global__ __launch_bounds__(kThreads, 2) void sr_partial_balanced_kernel(Partia
       attend_range<kPaged>(a, b, g, L, blk_lo * kBlock, min(blk_hi * kBlock, L), p - s0 / c);
       __syncthreads();                            // LDS of attend_range is reused by the next segment
     }
+    SR_STAMP(a.timeline, kTimelinePartialStamps, 7);
     return;
   }
   int carry = 0;
@@ -431,6 +448,7 @@ __global__ __launch_bounds__(kThreads, 2) void sr_partial_balanced_kernel(Partia
     for (int i = tid; i <= NG; i += kThreads) a.sched[2 + i] = start[i];
   }
   const int u_lo = p * c, u_hi = min(u_lo + c, U);
+  SR_STAMP(a.timeline, kTimelinePartialStamps, 3);
   if (u_lo >= u_hi) return;
   for (int i = tid; i < NG; i += kThreads)
     if (start[i] <= u_lo && u_lo < start[i + 1]) first_group = i;   // exactly one group holds u_lo
@@ -444,6 +462,7 @@ __global__ __launch_bounds__(kThreads, 2) void sr_partial_balanced_kernel(Partia
     attend_range<kPaged>(a, b, g, L, blk_lo * kBlock, min(blk_hi * kBlock, L), p - s0 / c);
     __syncthreads();                            // LDS of attend_range is reused by the next segment
   }
+  SR_STAMP(a.timeline, kTimelinePartialStamps, 7);
 }
 
 }  // namespace

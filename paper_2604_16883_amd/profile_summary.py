@@ -1,0 +1,159 @@
+"""Turns the raw rocprofv3 output of three profiled `bench.py --lean` runs of one workload into the short
+summary kept under profiles/ and into that workload's record of profiles/traffic.json (which bench.py reads
+for `roofline.traffic`).
+
+    python -m paper_2604_16883_amd.profile_summary <dir> <workload>
+
+<dir> holds, as written by the commands the summary itself lists:
+    trace/t_kernel_trace.csv, trace/t_kernel_stats.csv    rocprofv3 --kernel-trace --stats
+    fetch/f_counter_collection.csv                        rocprofv3 --pmc FETCH_SIZE
+    write/w_counter_collection.csv                        rocprofv3 --pmc WRITE_SIZE
+    trace.log                                             stdout of the traced run (bench.py's JSON line)
+The partial kernel's dispatches are attributed to the benchmark's modes by order: the JSON line carries how
+many launches each mode makes.  Counter units are scaled by the plain copy kernel of known size that every
+bench run dispatches once.
+"""
+from __future__ import annotations
+
+import collections
+import csv
+import glob
+import json
+import os
+import sys
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+COPY_BYTES = 1 << 30          # bench.py's calibration copy: 1 GiB read + 1 GiB written
+
+KERNELS = (("sr_partial", "sr_partial"), ("sr_combine", "sr_combine"), ("sr_probe_kernel", "sr_probe"),
+           ("sr_anchor", "sr_anchor"), ("sr_copy_probe", "sr_copy_probe"), ("sr_read_probe", "sr_read_probe"))
+
+
+def short(name: str):
+    for key, label in KERNELS:
+        if key in name:
+            return label
+    return None
+
+
+def find(base: str, pattern: str) -> str:
+    hits = sorted(glob.glob(os.path.join(base, "**", pattern), recursive=True))
+    if not hits:
+        raise SystemExit("no %s under %s" % (pattern, base))
+    return hits[0]
+
+
+def bench_line(path: str) -> dict:
+    for line in open(path):
+        line = line.strip()
+        if line.startswith("{") and '"metric"' in line:
+            return json.loads(line)
+    raise SystemExit("no benchmark JSON line in %s" % path)
+
+
+def split_by_plan(values, plan):
+    out, i = {}, 0
+    for label, n in plan:
+        out[label] = values[i:i + n]
+        i += n
+    if i != len(values):
+        raise SystemExit("dispatch plan covers %d launches, the profile has %d" % (i, len(values)))
+    return out
+
+
+def counters(path: str):
+    d = collections.defaultdict(list)
+    for r in csv.DictReader(open(path)):
+        s = short(r["Kernel_Name"])
+        if s:
+            d[s].append(float(r["Counter_Value"]))
+    return d
+
+
+def main(argv):
+    if len(argv) != 3:
+        raise SystemExit(__doc__)
+    base, wl = argv[1], argv[2]
+    from bench import kernel_source_sha          # the same hash bench.py checks the record against
+    line = bench_line(os.path.join(base, "trace.log"))
+    det = line["detail"][wl]
+    plan = det["dispatch_plan"]
+    steps, warmup = line["steps"], line["warmup"]
+    cmd = "python3 $R/bench.py --workload %s --lean --steps %d --warmup %d" % (wl, steps, warmup)
+    out = ["# rocprofv3 summary: sr_partial_balanced_kernel and sr_combine_kernel, workload %s (%s, bf16)" % (wl, det["description"]), "",
+           "Commands (run from /tmp with TMPDIR=/tmp on the MI355X box, R = repository root, D = $R/gpurun_out/prof_%s):" % wl, "",
+           "    rocprofv3 --kernel-trace --stats --output-format csv -d $D/trace -o t -- %s > $D/trace.log" % cmd,
+           "    rocprofv3 --pmc FETCH_SIZE --output-format csv -d $D/fetch -o f -- %s" % cmd,
+           "    rocprofv3 --pmc WRITE_SIZE --output-format csv -d $D/write -o w -- %s" % cmd,
+           "    python3 -m paper_2604_16883_amd.profile_summary $D %s" % wl, "",
+           "Each run launches the modes below in this order; per mode %d warm-up + %d timed + %d (step-time spread) + %d (per-kernel HIP "
+           "events) launches at most (the last two are capped at 200 and 100).  The routing probe is fused into the partial kernel, so no sr_probe_kernel is dispatched.  sr_read_probe / "
+           "sr_copy_probe are the benchmark's calibration kernels (2 GiB streaming read; 1 GiB copy of known traffic)."
+           % (warmup, steps, steps, steps), "",
+           "## kernel-trace --stats (durations in us, all dispatches of a kernel name)", "",
+           "| kernel | calls | avg | min | max |", "|---|---|---|---|---|"]
+    for r in csv.DictReader(open(find(base, "t_kernel_stats.csv"))):
+        s = short(r["Name"])
+        if s:
+            out.append("| %s | %s | %.1f | %.1f | %.1f |" % (s, r["Calls"], float(r["AverageNs"]) / 1e3, float(r["MinNs"]) / 1e3,
+                                                          float(r["MaxNs"]) / 1e3))
+    rows = sorted((r for r in csv.DictReader(open(find(base, "t_kernel_trace.csv")))), key=lambda r: int(r["Start_Timestamp"]))
+    dur_p = [(int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e3 for r in rows if short(r["Kernel_Name"]) == "sr_partial"]
+    dur_c = [(int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e3 for r in rows if short(r["Kernel_Name"]) == "sr_combine"]
+    # gap between the end of a partial kernel and the start of the merge kernel that follows it
+    gaps = []
+    for a, b in zip(rows, rows[1:]):
+        if short(a["Kernel_Name"]) == "sr_partial" and short(b["Kernel_Name"]) == "sr_combine":
+            gaps.append((int(b["Start_Timestamp"]) - int(a["End_Timestamp"])) / 1e3)
+    by_p, by_c, by_g = split_by_plan(dur_p, plan), split_by_plan(dur_c, plan), split_by_plan(gaps, plan)
+    f, w = counters(find(base, "f_counter_collection.csv")), counters(find(base, "w_counter_collection.csv"))
+    fscale, wscale = COPY_BYTES / f["sr_copy_probe"][0], COPY_BYTES / w["sr_copy_probe"][0]
+    f_p, w_p = split_by_plan(f["sr_partial"], plan), split_by_plan(w["sr_partial"], plan)
+    f_c, w_c = split_by_plan(f["sr_combine"], plan), split_by_plan(w["sr_combine"], plan)
+    out += ["", "## per mode: partial kernel (mean over the mode's dispatches, the first %d warm-up ones left out)" % warmup, "",
+            "Durations from the kernel trace; bench.py's own figure (HIP events attached to the launch) beside it.  Bytes: FETCH_SIZE / "
+            "WRITE_SIZE per dispatch scaled by the copy kernel (1 GiB read, 1 GiB written: FETCH_SIZE = %.0f, WRITE_SIZE = %.0f, so one "
+            "unit = %.1f B and %.1f B)." % (f["sr_copy_probe"][0], w["sr_copy_probe"][0], fscale, wscale), "",
+            "| mode | skip | trace us (mean / min) | bench events us | algorithmic MB | fetched MB | written MB | traffic / algorithmic | "
+            "GB/s on trace mean | of 8 TB/s | merge kernel us | gap partial->merge us |", "|---|---|---|---|---|---|---|---|---|---|---|---|"]
+
+    def mean(v):
+        return sum(v) / max(len(v), 1)
+
+    record = {}
+    for label, _ in plan:
+        m = det[label]
+        d = by_p[label][warmup:]
+        fb, wb = mean(f_p[label][warmup:]) * fscale, mean(w_p[label][warmup:]) * wscale
+        ab = m["algorithmic_bytes"]
+        out.append("| %s | %.3f | %.1f / %.1f | %.1f | %.2f | %.2f | %.2f | %.4f | %.0f | %.1f %% | %.1f | %.2f |" % (
+            label, m["skip_ratio"], mean(d), min(d), m["partial_us"], ab / 1e6, fb / 1e6, wb / 1e6, (fb + wb) / ab,
+            ab / mean(d) / 1e3, ab / mean(d) / 1e3 / 80.0, mean(by_c[label][warmup:]), mean(by_g[label][warmup:])))
+        record[label] = {"kernel": "sr_partial_balanced_kernel", "fetch_bytes": round(fb), "write_bytes": round(wb),
+                         "algorithmic_bytes": ab, "trace_us_mean": round(mean(d), 2), "trace_us_min": round(min(d), 2),
+                         "merge_fetch_bytes": round(mean(f_c[label][warmup:]) * fscale),
+                         "merge_write_bytes": round(mean(w_c[label][warmup:]) * wscale),
+                         "merge_trace_us_mean": round(mean(by_c[label][warmup:]), 2),
+                         "fetch_unit_bytes": round(fscale, 2), "write_unit_bytes": round(wscale, 2),
+                         "kernel_source_sha": kernel_source_sha(), "command": cmd}
+    out += ["", "Merge kernel traffic (fetched / written MB per dispatch): " +
+            "; ".join("%s %.2f / %.2f" % (label, record[label]["merge_fetch_bytes"] / 1e6, record[label]["merge_write_bytes"] / 1e6)
+                      for label, _ in plan) + ".", ""]
+    os.makedirs(os.path.join(ROOT, "profiles"), exist_ok=True)
+    md = os.path.join(ROOT, "profiles", "sr_partial_balanced_kernel_%s.md" % wl)
+    with open(md, "w") as fh:
+        fh.write("\n".join(out))
+    tj = os.path.join(ROOT, "profiles", "traffic.json")
+    try:
+        allrec = json.load(open(tj))
+    except (OSError, ValueError):
+        allrec = {}
+    allrec[wl] = record
+    with open(tj, "w") as fh:
+        json.dump(allrec, fh, indent=1, sort_keys=True)
+        fh.write("\n")
+    print("wrote", md, "and", tj)
+
+
+if __name__ == "__main__":
+    main(sys.argv)

@@ -70,7 +70,7 @@ static void check_valid(const sr_route_params& p) {
   CHECK(lay.off_sched < lay.off_lens && lay.off_lens < pl.workspace_bytes);
   CHECK(lay.off_ml % 256 == 0 && lay.off_score % 256 == 0 && lay.off_sched % 256 == 0 && lay.off_lens % 256 == 0);
   const int spec = combine_spec_rows(lay, (int)NG);
-  CHECK(spec >= 1 && spec <= 8);
+  CHECK(spec >= 1 && spec <= kCombineRows);
   // the whole argument check on fake, suitably aligned addresses
   sr_route_params q = p;
   q.workspace = (void*)0x7000000;
