@@ -217,25 +217,24 @@ class Case:
             for s in range(n_prof):
                 st[s] = self.call(p, s, profiled=True)
             launches += n_prof
-        else:                       # no per-kernel events for the paged entry point: whole step only
-            st[:, 1] = st[:, 3] = us
         torch.cuda.synchronize()
         m = self.mask.cpu().numpy()
         ab = algorithmic_bytes(self.w, self.sb.seq_lens, m, plan)
-        partial_us = float(np.mean(st[:, 1]))
+        # no per-kernel events for the paged entry point: whole step only
+        partial_us = float(np.mean(st[:, 1])) if self.layout is None else None
         return {
             "us_per_step": round(us, 2),
             "us_per_step_graph_replay": None if graph_us is None else round(graph_us, 2),
             "step_us_p10_p50_p90": [round(float(x), 2) for x in np.percentile(step_us, [10, 50, 90])],
             "probe_us": round(float(np.mean(st[:, 0])), 2),
-            "partial_us": round(partial_us, 2),
+            "partial_us": None if partial_us is None else round(partial_us, 2),
             "partial_us_p10_p50_p90": [round(float(x), 2) for x in np.percentile(st[:, 1], [10, 50, 90])],
-            "combine_us": round(float(np.mean(st[:, 2])), 2),
+            "combine_us": None if partial_us is None else round(float(np.mean(st[:, 2])), 2),
             "skip_ratio": round(float(m.mean()), 4),
             "active_groups": int((1 - m).sum()),
             "algorithmic_bytes": int(ab),
-            "partial_GBps": round(ab / partial_us / 1e3, 1),
-            "partial_frac_of_peak": round(ab / partial_us / 1e3 / HBM_PEAK_GBS, 4),
+            "partial_GBps": None if partial_us is None else round(ab / partial_us / 1e3, 1),
+            "partial_frac_of_peak": None if partial_us is None else round(ab / partial_us / 1e3 / HBM_PEAK_GBS, 4),
             "step_GBps": round(ab / us / 1e3, 1),
             "step_frac_of_peak": round(ab / us / 1e3 / HBM_PEAK_GBS, 4),
             "anchors": "prefill-cached k0 and k0_norm" if (cached_anchors and routing) else ("row 0 of the cache" if routing else "unused"),
@@ -405,31 +404,36 @@ def timeline_markdown(rep, read_gbs):
     return "\n".join(out)
 
 
+def _f(x, fmt="%.1f", scale=1.0):
+    return "n/a" if x is None else fmt % (x * scale)
+
+
 def results_markdown(line):
     """The result tables of the design notes, generated from one benchmark line."""
     det = line["detail"]
     out = ["<!-- generated by: python bench.py --markdown <this file>; do not edit -->", "",
+           "Benchmark results on one MI355X, %d timed steps after %d warm-up steps per mode (no per-kernel events exist for the paged entry point: n/a)." % (line["steps"], line["warmup"]), "",
            "Partial kernel (events attached to the launch) and whole step (wall clock), routed at tau = 0.55 on prefill-cached anchors:", "",
            "| workload | skip | bytes | partial kernel us | GB/s | of 8 TB/s | step us | step GB/s | of 8 TB/s | dense step us | speed-up |",
            "|---|---|---|---|---|---|---|---|---|---|---|"]
     for name in sorted(det):
         r = det[name]
         rt, dn = r["routed_tau0.55"], r["dense"]
-        out.append("| %s | %.3f | %.1f MB | %.1f | %.0f | %.1f %% | %.1f | %.0f | %.1f %% | %.1f | %.2fx |" % (
-            name, rt["skip_ratio"], rt["algorithmic_bytes"] / 1e6, rt["partial_us"], rt["partial_GBps"], 100 * rt["partial_frac_of_peak"],
-            rt["us_per_step"], rt["step_GBps"], 100 * rt["step_frac_of_peak"], dn["us_per_step"], r["routed_vs_dense_speedup"]))
+        out.append("| %s | %.3f | %.1f MB | %s | %s | %s %% | %.1f | %.0f | %.1f %% | %.1f | %.2fx |" % (
+            name, rt["skip_ratio"], rt["algorithmic_bytes"] / 1e6, _f(rt["partial_us"]), _f(rt["partial_GBps"], "%.0f"),
+            _f(rt["partial_frac_of_peak"], "%.1f", 100), rt["us_per_step"], rt["step_GBps"], 100 * rt["step_frac_of_peak"], dn["us_per_step"], r["routed_vs_dense_speedup"]))
     out += ["", "Dense Split-K (routing off) on the same inputs:", "",
             "| workload | bytes | partial kernel us | of 8 TB/s | step us | of 8 TB/s |", "|---|---|---|---|---|---|"]
     for name in sorted(det):
         dn = det[name]["dense"]
-        out.append("| %s | %.1f MB | %.1f | %.1f %% | %.1f | %.1f %% |" % (
-            name, dn["algorithmic_bytes"] / 1e6, dn["partial_us"], 100 * dn["partial_frac_of_peak"], dn["us_per_step"],
+        out.append("| %s | %.1f MB | %s | %s %% | %.1f | %.1f %% |" % (
+            name, dn["algorithmic_bytes"] / 1e6, _f(dn["partial_us"]), _f(dn["partial_frac_of_peak"], "%.1f", 100), dn["us_per_step"],
             100 * dn["step_frac_of_peak"]))
     out += ["", "Other modes (us per step):", "", "| workload | mode | skip | step us | partial kernel us | merge kernel us |", "|---|---|---|---|---|---|"]
     for name in sorted(det):
         for mode, r in det[name].items():
             if isinstance(r, dict) and "us_per_step" in r and mode not in ("routed_tau0.55", "dense"):
-                out.append("| %s | %s | %.3f | %.1f | %.1f | %.1f |" % (name, mode, r["skip_ratio"], r["us_per_step"], r["partial_us"], r["combine_us"]))
+                out.append("| %s | %s | %.3f | %.1f | %s | %s |" % (name, mode, r["skip_ratio"], r["us_per_step"], _f(r["partial_us"]), _f(r["combine_us"])))
     if line.get("seeds"):
         out += ["", "c3 over repetition seeds (routed, tau = 0.55):", "", "| seed | skip | bytes | step us | step of 8 TB/s | partial kernel of 8 TB/s |",
                 "|---|---|---|---|---|---|"]
@@ -576,7 +580,9 @@ def main():
         torch.cuda.empty_cache()
 
     routed = main_res["routed_tau0.55"]
-    achieved = routed["partial_GBps"]
+    # the paged entry point has no per-kernel events: the whole step stands in for the kernel there
+    achieved = routed["partial_GBps"] or routed["step_GBps"]
+    dense_achieved = main_res["dense"]["partial_GBps"] or main_res["dense"]["step_GBps"]
     traffic, traffic_src = (None, "not the profiled configuration") if (a.num_splits or a.paged) else measured_traffic(a.workload, "routed_tau0.55")
     traffic_bytes = None if traffic is None else traffic["fetch_bytes"] + traffic["write_bytes"]
     line = {
@@ -596,10 +602,9 @@ def main():
                      "traffic_ratio": None if traffic_bytes is None else round(traffic_bytes / routed["algorithmic_bytes"], 4),
                      "traffic_source": traffic_src,
                      "algorithmic_bytes_per_launch": routed["algorithmic_bytes"],
-                     "kernel_us": routed["partial_us"],
+                     "kernel_us": routed["partial_us"] or routed["us_per_step"],
                      "step_achieved": routed["step_GBps"], "step_frac": routed["step_frac_of_peak"],
-                     "dense_achieved": main_res["dense"]["partial_GBps"],
-                     "dense_frac": main_res["dense"]["partial_frac_of_peak"],
+                     "dense_achieved": dense_achieved, "dense_frac": round(dense_achieved / HBM_PEAK_GBS, 4),
                      "stream_read_probe_GBps": round(calib, 1)},
         "cpu_baseline": cpu,
         "dense_us_per_step": main_res["dense"]["us_per_step"],

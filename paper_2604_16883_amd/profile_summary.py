@@ -111,11 +111,13 @@ def main(argv):
     f_p, w_p = split_by_plan(f["sr_partial"], plan), split_by_plan(w["sr_partial"], plan)
     f_c, w_c = split_by_plan(f["sr_combine"], plan), split_by_plan(w["sr_combine"], plan)
     out += ["", "## per mode: partial kernel (mean over the mode's dispatches, the first %d warm-up ones left out)" % warmup, "",
-            "Durations from the kernel trace; bench.py's own figure (HIP events attached to the launch) beside it.  Bytes: FETCH_SIZE / "
+            "Durations from the kernel trace (dispatch begin to end, the interval bench.py's HIP events attached to the launch "
+            "measure when no profiler runs; under the profiler those events read about 10 us more and are not shown).  The gap is "
+            "between the trace's end of the partial kernel and begin of the merge kernel.  Bytes: FETCH_SIZE / "
             "WRITE_SIZE per dispatch scaled by the copy kernel (1 GiB read, 1 GiB written: FETCH_SIZE = %.0f, WRITE_SIZE = %.0f, so one "
             "unit = %.1f B and %.1f B)." % (f["sr_copy_probe"][0], w["sr_copy_probe"][0], fscale, wscale), "",
-            "| mode | skip | trace us (mean / min) | bench events us | algorithmic MB | fetched MB | written MB | traffic / algorithmic | "
-            "GB/s on trace mean | of 8 TB/s | merge kernel us | gap partial->merge us |", "|---|---|---|---|---|---|---|---|---|---|---|---|"]
+            "| mode | skip | trace us (mean / min) | algorithmic MB | fetched MB | written MB | traffic / algorithmic | "
+            "GB/s on trace mean | of 8 TB/s | merge kernel us | gap partial->merge us |", "|---|---|---|---|---|---|---|---|---|---|---|"]
 
     def mean(v):
         return sum(v) / max(len(v), 1)
@@ -126,8 +128,8 @@ def main(argv):
         d = by_p[label][warmup:]
         fb, wb = mean(f_p[label][warmup:]) * fscale, mean(w_p[label][warmup:]) * wscale
         ab = m["algorithmic_bytes"]
-        out.append("| %s | %.3f | %.1f / %.1f | %.1f | %.2f | %.2f | %.2f | %.4f | %.0f | %.1f %% | %.1f | %.2f |" % (
-            label, m["skip_ratio"], mean(d), min(d), m["partial_us"], ab / 1e6, fb / 1e6, wb / 1e6, (fb + wb) / ab,
+        out.append("| %s | %.3f | %.1f / %.1f | %.2f | %.2f | %.2f | %.4f | %.0f | %.1f %% | %.1f | %.2f |" % (
+            label, m["skip_ratio"], mean(d), min(d), ab / 1e6, fb / 1e6, wb / 1e6, (fb + wb) / ab,
             ab / mean(d) / 1e3, ab / mean(d) / 1e3 / 80.0, mean(by_c[label][warmup:]), mean(by_g[label][warmup:])))
         record[label] = {"kernel": "sr_partial_balanced_kernel", "fetch_bytes": round(fb), "write_bytes": round(wb),
                          "algorithmic_bytes": ab, "trace_us_mean": round(mean(d), 2), "trace_us_min": round(min(d), 2),

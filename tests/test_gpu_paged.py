@@ -64,3 +64,30 @@ def test_paged_full_size_c1():
     res["probe_mask"], res["score"] = cont["probe_mask"], cont["score"]
     print("c1 paged full", gu.compare(res, ref, w.group_size, "c1 paged full"), flush=True)
     assert np.array_equal(res["out_bits"], cont["out_bits"])
+
+
+def test_full_size_ragged_batch_contiguous_and_paged():
+    """A 128K-class batch with one long and several short sequences (32768, 20011, 4097 and 65 tokens, the
+    shape the benchmark times as c1_ragged): the balanced schedule deals the long sequence's blocks over most
+    workgroups while the short ones share a few, tails fall inside a block and inside a page.  Contiguous and
+    paged (256-token pages, random page order), routed at three thresholds and dense, element by element
+    against the oracle; the paged result equals the contiguous one bit for bit."""
+    lens = [32768, 20011, 4097, 65]
+    w = synth.WORKLOADS["c1"].scaled(max(lens), batch=len(lens))
+    sb = synth.generate(w, seq_lens=lens)
+    kp, table = synth.to_pages(sb.k, sb.seq_lens, 256, seed=17)
+    vp, _ = synth.to_pages(sb.v, sb.seq_lens, 256, seed=17)
+    dev = None
+    seen = set()
+    for kw in (dict(tau_coef=(0, 0, 0, 0.55)), dict(tau_coef=(0, 0, 0, 0.45)), dict(tau_coef=(0, 0, 0, 0.7)), dict(routing_enabled=False)):
+        print("ragged full", kw, flush=True)
+        ref = oracle.decode(sb.q, sb.k, sb.v, sb.seq_lens, want_dense=True, **kw)
+        cont = gu.run_hip(sb.q, sb.k, sb.v, sb.seq_lens, dev=dev, **kw)
+        dev = cont["dev"]
+        rep = gu.compare(cont, ref, w.group_size, "ragged full %s" % kw)
+        assert cont["plan"].schedule == 1
+        res = run_paged(sb, kp, vp, table, 256, **kw)
+        assert np.array_equal(res["out_bits"], cont["out_bits"]) and np.array_equal(res["mask"], cont["mask"])
+        seen.add(rep["skip_ratio"])
+        print("ragged full", kw, rep, flush=True)
+    assert len(seen) >= 3
