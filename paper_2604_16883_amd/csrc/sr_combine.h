@@ -33,8 +33,11 @@ struct CombineArgs {
 };
 
 // One pass: every wavefront keeps a running (max, sum, weighted rows) over the records it owns
-// (record s belongs to wavefront s % 16) and the 16 wavefronts are merged through LDS.  A wavefront
-// holds kCombineRows records in flight (16 measured 1 us slower per step than 8, 2 and 4 the same as 8).
+// (record s belongs to wavefront s % 16, to its lower or upper half by (s / 16) % 2) and the 16
+// wavefronts are merged through LDS.  A half wavefront reads a whole 512-byte record row per load (32
+// lanes x 16 bytes) and holds kCombineRows of them in flight, so one sweep takes 32 kCombineRows = 128
+// records (measured: 8-byte loads per lane and 8 rows in flight cost heads with more than 128 records a
+// third round trip, 0.9 us on the 200K-context workload; 8 rows of 16-byte loads cost every launch 0.3 us).
 // The first records of every wavefront (spec of them) are requested at kernel entry, before the number
 // of records is known (it takes a load of the mask and of the schedule to know it); when spec covers the
 // head's records the merge costs one memory round trip.  What was fetched beyond the last record is
@@ -50,14 +53,18 @@ __global__ __launch_bounds__(kCombineThreads) void sr_combine_kernel(CombineArgs
   const int b = bh / a.Hq, h = bh - b * a.Hq, g = h / a.G;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const float2* ml = reinterpret_cast<const float2*>(a.part_ml) + (size_t)bh * a.slots;
-  const float2* po = reinterpret_cast<const float2*>(a.part_o) + (size_t)bh * a.slots * (kD / 2);
-  float2 st[UN], o[UN];
+  // Each half of a wavefront reads one record per load: 32 lanes x 16 bytes = one 512-byte row.  Row u of
+  // half hf of wavefront w is record w + 16 (2u + hf): one sweep of UN rows covers 32 UN records per wavefront pair.
+  const float4* po = reinterpret_cast<const float4*>(a.part_o) + (size_t)bh * a.slots * (kD / 4);
+  const int hf = lane >> 5, l32 = lane & 31;
+  float2 st[UN];
+  float4 o[UN];
 #pragma unroll
   for (int u = 0; u < UN; ++u) {                 // slots that do not exist are read as the last one and dropped below
     if (u < a.spec) {
-      const int s = min(wave + u * NW, a.slots - 1);
+      const int s = min(wave + NW * (2 * u + hf), a.slots - 1);
       st[u] = ml[s];
-      o[u] = po[(size_t)s * (kD / 2) + lane];
+      o[u] = po[(size_t)s * (kD / 4) + l32];
     }
   }
   const int L = clamp_len(a.seq_lens[b], a.Lmax);
@@ -93,37 +100,50 @@ __global__ __launch_bounds__(kCombineThreads) void sr_combine_kernel(CombineArgs
   __shared__ float red_l[NW];
   __shared__ float2 red_o[NW][64];
   float m_run = -INFINITY, lsum = 0.f;
-  float2 acc = make_float2(0.f, 0.f);
-  for (int s0 = wave; s0 < n; s0 += NW * UN) {   // UN rows in flight per wavefront
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int s0 = wave; s0 < n; s0 += NW * 2 * UN) {   // UN rows in flight per half wavefront
     const int have = s0 == wave ? a.spec : 0;    // rows of this batch that are already here
 #pragma unroll
     for (int u = 0; u < UN; ++u) {
-      if (u >= have && s0 + u * NW < n) {
-        const int s = s0 + u * NW;
+      const int s = s0 + NW * (2 * u + hf);
+      if (u >= have && s < n) {
         st[u] = ml[s];
-        o[u] = po[(size_t)s * (kD / 2) + lane];
+        o[u] = po[(size_t)s * (kD / 4) + l32];
       }
     }
     float bm = m_run;
 #pragma unroll
     for (int u = 0; u < UN; ++u) {
-      if (s0 + u * NW >= n) st[u] = make_float2(-INFINITY, 0.f);
+      if (s0 + NW * (2 * u + hf) >= n) st[u] = make_float2(-INFINITY, 0.f);
       bm = fmaxf(bm, st[u].x);
     }
-    const float keep = __builtin_amdgcn_exp2f(m_run - bm);   // bm is finite: row s0 exists
-    acc.x *= keep; acc.y *= keep; lsum *= keep;
+    // the upper half may own no record at all: everything of it is then weighted 0
+    const float keep = m_run > -INFINITY ? __builtin_amdgcn_exp2f(m_run - bm) : 0.f;
+    acc.x *= keep; acc.y *= keep; acc.z *= keep; acc.w *= keep; lsum *= keep;
 #pragma unroll
     for (int u = 0; u < UN; ++u) {
-      const bool ok = s0 + u * NW < n;
-      const float wt = __builtin_amdgcn_exp2f(st[u].x - bm);
+      const bool ok = s0 + NW * (2 * u + hf) < n;
+      const float wt = ok ? __builtin_amdgcn_exp2f(st[u].x - bm) : 0.f;
       acc.x += ok ? wt * o[u].x : 0.f;
       acc.y += ok ? wt * o[u].y : 0.f;
-      lsum += wt * st[u].y;
+      acc.z += ok ? wt * o[u].z : 0.f;
+      acc.w += ok ? wt * o[u].w : 0.f;
+      lsum += ok ? wt * st[u].y : 0.f;
     }
     m_run = bm;
   }
+  {   // fold the upper half into the lower one (lane l and lane l + 32 hold the same 4 columns)
+    const float m_o = __shfl_xor(m_run, 32, 64), l_o = __shfl_xor(lsum, 32, 64);
+    const float ax = __shfl_xor(acc.x, 32, 64), ay = __shfl_xor(acc.y, 32, 64), az = __shfl_xor(acc.z, 32, 64), aw = __shfl_xor(acc.w, 32, 64);
+    const float mm = fmaxf(m_run, m_o);
+    const float w_s = m_run > -INFINITY ? __builtin_amdgcn_exp2f(m_run - mm) : 0.f;
+    const float w_o = m_o > -INFINITY ? __builtin_amdgcn_exp2f(m_o - mm) : 0.f;
+    acc.x = w_s * acc.x + w_o * ax; acc.y = w_s * acc.y + w_o * ay; acc.z = w_s * acc.z + w_o * az; acc.w = w_s * acc.w + w_o * aw;
+    lsum = w_s * lsum + w_o * l_o;
+    m_run = mm;
+  }
   SR_STAMP(tl, kTimelineMergeStamps, 1);
-  red_o[wave][lane] = acc;
+  if (hf == 0) *reinterpret_cast<float4*>(&red_o[wave][2 * l32]) = acc;     // columns 4 l32 .. 4 l32 + 3
   if (lane == 0) { red_m[wave] = m_run; red_l[wave] = lsum; }
   __syncthreads();
   SR_STAMP(tl, kTimelineMergeStamps, 2);

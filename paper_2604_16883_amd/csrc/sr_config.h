@@ -37,9 +37,9 @@ constexpr int kMaxGroup = 16;        // query heads per KV group that fit the MF
 constexpr int kChunkUnit = kBlock * kWaves;
 constexpr int kCombineThreads = 1024;
 #ifndef SR_COMBINE_ROWS
-#define SR_COMBINE_ROWS 8
+#define SR_COMBINE_ROWS 4
 #endif
-constexpr int kCombineRows = SR_COMBINE_ROWS;   // partial records a merge wavefront keeps in flight
+constexpr int kCombineRows = SR_COMBINE_ROWS;   // record rows a half wavefront of the merge keeps in flight
 constexpr int kBalancedGrid = SR_GRID;   // persistent workgroups of the balanced schedule: one per compute unit
 constexpr int kMaxSchedGroups = 2048;  // (sequence, KV group) pairs the balanced schedule scans in LDS
 constexpr int kMaxFusedHeads = 512;    // query heads (all sequences) the balanced kernel probes itself

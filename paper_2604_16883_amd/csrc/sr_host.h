@@ -142,8 +142,8 @@ inline int check_paged_args(const int32_t* block_table, const sr_paged_layout* l
 // these rows, Sink Groups' heads included.
 inline int combine_spec_rows(const Layout& lay, int NG) {
   const int expect = lay.plan.schedule == 1 ? kBalancedGrid / NG + 1 : lay.plan.num_splits;
-  const int waves = kCombineThreads / 64;
-  const int rows = (expect + waves - 1) / waves;
+  const int per_row = 2 * (kCombineThreads / 64);     // one load instruction of the 16 wavefronts covers 32 records
+  const int rows = (expect + per_row - 1) / per_row;
   return rows < 1 ? 1 : (rows > kCombineRows ? kCombineRows : rows);
 }
 
