@@ -204,6 +204,10 @@ def test_compute_call_without_gpu_fails_loudly():
         pytest.skip("a GPU is present")
     # valid arguments, no device: the HIP launch fails and the library says so; nothing falls back to the CPU
     assert call() == B.SR_ERR_HIP
+    # the allocation-free entry point needs the device address of its scratch array: no device, no address
+    assert B.sinkrouter_decode_static(FAKE["q"], FAKE["k"], FAKE["v"], FAKE["sl"], B.make_route_params(1, 32, 8, 4096),
+                                      FAKE["out"], FAKE["mask"], check=False) == B.SR_ERR_HIP
+    assert B.sinkrouter_timeline_bytes() == 0           # the product build carries no stamps
     with pytest.raises(B.SinkRouterError):
         B.sinkrouter_decode(FAKE["q"], FAKE["k"], FAKE["v"], FAKE["sl"],
                             B.make_route_params(1, 32, 8, 4096, workspace=FAKE["ws"], workspace_bytes=1 << 30),
