@@ -528,7 +528,9 @@ def main():
         sys.exit(3)
     if a.timeline:
         os.environ["SINKROUTER_LIB"] = os.path.join(ROOT, "paper_2604_16883_amd", "libsinkrouter_timeline.so")
-    from paper_2604_16883_amd import binding
+    from paper_2604_16883_amd import binding, build
+    if not a.timeline:
+        build.ensure_built()
     binding.load()
     if a.lean:
         a.also, a.no_extras, a.no_cpu_baseline = "", True, True

@@ -65,6 +65,14 @@ def build_library(verbose: bool = False, extra=(), timeline: bool = False) -> st
     return LIB
 
 
+def ensure_built() -> str:
+    """For the tests, the smoke check and the benchmark: the library as it stands if it has been built, else one
+    build now.  (The binding itself never builds and never falls back: without the library it raises.)"""
+    if not os.path.exists(LIB):
+        build_library()
+    return LIB
+
+
 def kernel_resource_usage(log: str) -> dict:
     """Parse clang's kernel-resource-usage remarks: {kernel name: {field: value}}."""
     import re
