@@ -228,7 +228,8 @@ int sinkrouter_decode_paged(const void* q, const void* k_pages, const void* v_pa
  * params->workspace and params->workspace_bytes are ignored: the partial records live in a device
  * array of SINKROUTER_STATIC_SCRATCH_BYTES that is part of the library's code object (every GPU
  * the library runs on holds it until the process ends).  The call allocates and frees nothing; the
- * array's address is looked up on the first call on each device.  A shape whose
+ * array's address is looked up on the first call on each device, so make that first call outside
+ * stream capture.  A shape whose
  * sinkrouter_plan().workspace_bytes exceeds SINKROUTER_STATIC_SCRATCH_BYTES returns
  * SR_ERR_STATIC_LIMIT (checked on the host, before any HIP call); all five benchmark shapes fit.
  * Nothing in the array has to start at zero (every record is written before it is read), so

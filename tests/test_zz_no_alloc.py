@@ -52,3 +52,45 @@ def test_static_scratch_rejects_shapes_beyond_its_size():
     assert binding.sinkrouter_plan(p).workspace_bytes > binding.STATIC_SCRATCH_BYTES
     rc = binding.sinkrouter_decode_static(1 << 16, 1 << 17, 1 << 18, 1 << 19, p, 1 << 20, 1 << 21, check=False)
     assert rc == binding.SR_ERR_STATIC_LIMIT
+
+
+def test_static_scratch_call_captured_into_a_graph():
+    """The callers this entry point is for: a HIP graph captured around it (after one eager call on the device, which
+    looks the scratch array's address up) replays to the eager result every time, with other work between the replays."""
+    import torch
+    w = synth.WORKLOADS["c1"].scaled(2500, batch=2)
+    sb = synth.generate(w, seed=23, seq_lens=[2500, 1301])
+    B, Hq, Hkv, Lmax = w.batch, w.n_q_heads, w.n_kv_heads, sb.max_seq_len
+    tq, tk, tv, tsl = gu.to_dev(sb.q), gu.to_dev(sb.k), gu.to_dev(sb.v), gu.to_dev(sb.seq_lens)
+    p = binding.make_route_params(B, Hq, Hkv, Lmax)
+    out = torch.empty((B, Hq, 128), dtype=torch.int16, device="cuda")
+    mask = torch.empty((B, Hkv), dtype=torch.uint8, device="cuda")
+
+    def step():
+        binding.sinkrouter_decode_static(tq, tk, tv, tsl, p, out, mask)
+
+    step()
+    torch.cuda.synchronize()
+    eager_out, eager_mask = out.clone(), mask.clone()
+    want = gu.run_hip(sb.q, sb.k, sb.v, sb.seq_lens)
+    assert np.array_equal(eager_out.cpu().numpy().view(np.uint16), want["out_bits"])
+    assert 0 < int(eager_mask.sum()) < eager_mask.numel()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step()
+    other = synth.generate(synth.WORKLOADS["c0"].scaled(900), seed=5)
+    for rep in range(4):
+        out.fill_(-1)
+        mask.fill_(9)
+        gu.run_hip(other.q, other.k, other.v, other.seq_lens)        # eager work with its own workspace in between
+        run_static(other)                                            # and a call that overwrites the shared scratch
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager_out), "replay %d differs from the eager result" % rep
+        assert torch.equal(mask, eager_mask)
