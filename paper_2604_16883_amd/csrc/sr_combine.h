@@ -67,14 +67,24 @@ __global__ __launch_bounds__(kCombineThreads) void sr_combine_kernel(CombineArgs
       o[u] = po[(size_t)s * (kD / 4) + l32];
     }
   }
-  const int L = clamp_len(a.seq_lens[b], a.Lmax);
+  // Everything the head's record count depends on is requested here, unconditionally and together with the
+  // speculative rows, as vector loads: the sequence length and the three schedule entries by lanes 0..3 of
+  // one load instruction (broadcast afterwards), the mask byte by another.  One memory round trip covers
+  // them all; a mask test in front of the schedule loads, or scalar loads (which have to be waited for
+  // one batch at a time), made it three dependent ones.
   const int bg = b * a.Hkv + g;
+  const int32_t* src = a.seq_lens + b;                                       // lane 0 (and the idle lanes)
+  if (a.sched && lane >= 1 && lane <= 3) src = a.sched + (lane == 1 ? 1 : bg + lane);   // c, start[bg], start[bg + 1]
+  const int word = *src;
+  const int sink = a.mask[bg];
+  const int len_raw = __builtin_amdgcn_readlane(word, 0);
+  const int c = __builtin_amdgcn_readlane(word, 1), u0 = __builtin_amdgcn_readlane(word, 2), u1 = __builtin_amdgcn_readlane(word, 3);
+  const int L = clamp_len(len_raw, a.Lmax);
   uint32_t* orow = a.out + (size_t)bh * (kD / 2);
   int n = 0;                                     // partial records of this head
-  if (!a.mask[bg] && L > 0) {
+  if (!sink && L > 0) {
     if (a.sched) {
-      const int c = a.sched[1], s0 = a.sched[2 + bg], s1 = a.sched[3 + bg];
-      if (s1 > s0) n = (s1 - 1) / c - s0 / c + 1;
+      if (u1 > u0) n = (u1 - 1) / c - u0 / c + 1;
     } else {
       n = (L + a.chunk - 1) / a.chunk;
     }
