@@ -161,6 +161,7 @@ int decode_impl(const void* q, const void* k, const void* v, const int32_t* seq_
     a.k0 = p->k0; a.k0_norm = p->k0_norm; a.group_score = score; a.rule = make_rule(p);
     a.Hq = p->n_q_heads; a.Hkv = p->n_kv_heads; a.G = lay.plan.group_size; a.Lmax = p->max_seq_len;
     a.NG = p->batch * p->n_kv_heads;
+    a.g_magic = div_magic((uint32_t)a.G); a.hkv_magic = div_magic((uint32_t)a.Hkv);
     a.chunk = lay.plan.chunk_tokens; a.slots = lay.plan.slots_per_head;
     a.scale_log2 = scale_log2_of(p);
     a.pm = pm;

@@ -54,6 +54,18 @@ constexpr int kTimelinePartialStamps = 8, kTimelineMergeStamps = 4, kTimelineMer
 constexpr size_t kTimelineBytes =
     SR_TIMELINE ? ((size_t)kBalancedGrid * kTimelinePartialStamps + (size_t)kTimelineMergeGroups * kTimelineMergeStamps) * 8 : 0;
 
+// Division by a run-time constant as one multiply: magic = ceil(2^32 / d) made on the host, x / d == umulhi(x, magic)
+// for every x with x * d < 2^32 (d == 1 is marked by magic 0).  The kernels use it where a workgroup's first loads wait
+// for a quotient (head -> group, group -> sequence).
+inline uint32_t div_magic(uint32_t d) { return d <= 1 ? 0u : (uint32_t)((((uint64_t)1) << 32) / d + 1); }
+SR_HD uint32_t div_by(uint32_t x, uint32_t magic) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  return magic ? __umulhi(x, magic) : x;
+#else
+  return magic ? (uint32_t)(((uint64_t)x * magic) >> 32) : x;
+#endif
+}
+
 // seq_lens[b] as the kernels use it: values outside [0, L_max] are clamped.
 SR_HD int clamp_len(int L, int Lmax) { return L < 0 ? 0 : (L > Lmax ? Lmax : L); }
 

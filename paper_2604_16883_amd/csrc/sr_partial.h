@@ -31,6 +31,7 @@ struct PartialArgs {
   float* part_ml;   // [B*Hq, slots, 2]  m (log2 domain), l
   int32_t* sched;   // balanced schedule only: U, c, start[0..NG]
   int Hq, Hkv, G, Lmax, NG;
+  uint32_t g_magic, hkv_magic;   // div_magic(G), div_magic(Hkv)
   int chunk;        // fixed schedule: tokens per chunk
   int slots;        // partial records per head
   float scale_log2; // softmax scale * log2(e)
@@ -336,10 +337,14 @@ __global__ __launch_bounds__(kThreads, 2) void sr_partial_balanced_kernel(Partia
   // anchor loads are in flight together (one memory round trip at kernel start instead of two)
   SR_STAMP(a.timeline, kTimelinePartialStamps, 0);
   int len_first = 0;
-  if (tid < NG) len_first = a.seq_lens[tid / a.Hkv];
+  if (tid < NG) len_first = a.seq_lens[div_by(tid, a.hkv_magic)];
   if (kFused && a.rule.routing) {
     const int NH = NG * G, lane4 = tid & 3;
     const uint4* q4 = reinterpret_cast<const uint4*>(a.q);
+    // anchor of (sequence, group) i: row i of the separate K_0 tensor, else token 0 of its cache (contiguous caches:
+    // a fixed stride; paged ones go through the block table)
+    const uint4* kbase = static_cast<const uint4*>(a.k0 ? a.k0 : static_cast<const void*>(a.k));
+    const size_t kstride = a.k0 ? (size_t)(kD / 8) : (size_t)a.Lmax * (kD / 8);
     for (int h0 = 0; h0 < NH; h0 += kThreads / 2) {      // kThreads/4 heads per sweep, two sweeps in flight
       uint4 qw[2][4], kw[2][4];
       float kn[2];
@@ -347,9 +352,9 @@ __global__ __launch_bounds__(kThreads, 2) void sr_partial_balanced_kernel(Partia
       for (int u = 0; u < 2; ++u) {
         int hd = h0 + (kThreads / 4) * u + (tid >> 2);
         hd = hd < NH ? hd : NH - 1;
-        const int i = hd / G;
+        const int i = div_by(hd, a.g_magic);
         const uint4* qrow = q4 + (size_t)hd * (kD / 8);
-        const uint4* krow = anchor_row(a.k, a.k0, i, a.Lmax, a.Hkv, a.pm);
+        const uint4* krow = (kPaged && !a.k0) ? anchor_row(a.k, a.k0, i, a.Lmax, a.Hkv, a.pm) : kbase + (size_t)i * kstride;
 #pragma unroll
         for (int j = 0; j < 4; ++j) { qw[u][j] = qrow[lane4 + 4 * j]; kw[u][j] = krow[lane4 + 4 * j]; }
         kn[u] = a.k0_norm ? a.k0_norm[i] : -1.f;

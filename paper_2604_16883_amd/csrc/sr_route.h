@@ -27,6 +27,11 @@ __device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float acc) {
   return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a), __builtin_bit_cast(bf16x2, b), acc, false);
 }
 
+// Square root for the norms of Eq. 7 and Eq. 11: the hardware instruction (1 ulp), not the correctly rounded
+// library sequence; the probe sits in front of every workgroup's first K/V load, so its instruction count matters.
+// The probe, the fused probe and the anchor kernel all take their norms from here, so they agree bit for bit.
+__device__ __forceinline__ float norm_of(float sumsq) { return __builtin_amdgcn_sqrtf(sumsq); }
+
 // Sum of squares of one 256-byte row held by a quad (4 chunks per lane): ||K_0||^2 of Eq. 7.
 __device__ __forceinline__ float quad_sumsq(const uint4 (&kw)[4]) {
   float kk = 0.f;
@@ -55,17 +60,17 @@ __device__ __forceinline__ float head_cosine(const uint4 (&qw)[4], const uint4 (
   }
   dot = quad_swap_add<0xB1>(dot); qq = quad_swap_add<0xB1>(qq);   // quad_perm [1,0,3,2]
   dot = quad_swap_add<0x4E>(dot); qq = quad_swap_add<0x4E>(qq);   // quad_perm [2,3,0,1]
-  const float nk = anchor_norm >= 0.f ? anchor_norm : sqrtf(quad_sumsq(kw));
-  const float den = sqrtf(qq) * nk;
-  return (den > 0.f) ? dot / den : 0.f;
+  const float nk = anchor_norm >= 0.f ? anchor_norm : norm_of(quad_sumsq(kw));
+  const float den = norm_of(qq) * nk;
+  return (den > 0.f) ? dot * __builtin_amdgcn_rcpf(den) : 0.f;
 }
 
 // Eq. 12-13 and the cubic threshold of Appendix A.  cosines: the G values of the group, in head order.
 __device__ __forceinline__ bool route_decide(const float* cosines, int G, int L, const RouteRule& r, float* S_out) {
   float S = 0.f;
   for (int j = 0; j < G; ++j) S += cosines[j];
-  S /= (float)G;
-  const float x = r.len_norm > 0.f ? (float)L / r.len_norm : 0.f;
+  S *= __builtin_amdgcn_rcpf((float)G);        // hardware reciprocal (1 ulp; exact for the usual power-of-two G)
+  const float x = r.len_norm > 0.f ? (float)L * __builtin_amdgcn_rcpf(r.len_norm) : 0.f;
   const float tau = ((r.tau[0] * x + r.tau[1]) * x + r.tau[2]) * x + r.tau[3];
   *S_out = S;
   return r.routing && L > 0 && S > tau;       // strict; NaN compares false, so the group stays active
@@ -126,7 +131,7 @@ __global__ __launch_bounds__(64) void sr_anchor_kernel(const void* k_cache, uint
 #pragma unroll
       for (int j = 0; j < 4; ++j) k0_out[(size_t)bg * (kD / 8) + lane4 + 4 * j] = kw[j];
     }
-    if (k0_norm_out && lane4 == 0) k0_norm_out[bg] = sqrtf(kk);
+    if (k0_norm_out && lane4 == 0) k0_norm_out[bg] = norm_of(kk);
   }
 }
 

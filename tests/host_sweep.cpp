@@ -126,6 +126,13 @@ static void check_pages() {
         ((((size_t)(INT_MAX - 1) * 65535 + 65534) << 12) + 4095) * 16);
   CHECK(clamp_len(INT_MIN, 5) == 0 && clamp_len(-1, 5) == 0 && clamp_len(0, 5) == 0 && clamp_len(5, 5) == 5);
   CHECK(clamp_len(6, 5) == 5 && clamp_len(INT_MAX, 1 << 24) == (1 << 24));
+  // division by multiplication, on the domains the kernels use (x * d < 2^32)
+  for (uint32_t d : {1u, 2u, 3u, 4u, 5u, 7u, 8u, 12u, 16u, 40u, 255u, 256u, 257u, 2047u, 2048u, 40000u, 65535u}) {
+    const uint32_t m = div_magic(d);
+    const uint32_t top = (uint32_t)(((uint64_t)1 << 32) / d);
+    for (uint32_t x = 0; x < 70000u && x < top; ++x) CHECK(div_by(x, m) == x / d);
+    for (uint32_t x = top > 5000u ? top - 5000u : 0u; x < top; ++x) CHECK(div_by(x, m) == x / d);
+  }
   sr_paged_layout lay = {(uint32_t)sizeof(sr_paged_layout), 64, 4, 3};
   sr_route_params p = shape(1, 8, 2, 256, 0);
   PageMap out;
