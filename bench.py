@@ -71,10 +71,20 @@ def partial_records(w, seq_lens, mask, plan):
         return sum(G * ((int(seq_lens[b]) + plan.chunk_tokens - 1) // plan.chunk_tokens)
                    for b in range(B) for g in range(Hkv) if not mask[b, g])
     units = [0 if mask[b, g] else (int(seq_lens[b]) + 63) // 64 for b in range(B) for g in range(Hkv)]
-    U = sum(units)
+    U, P = sum(units), plan.partial_grid
+    A = sum(1 for u in units if u)
     if U == 0:
         return 0
-    c = (U + plan.partial_grid - 1) // plan.partial_grid
+    if 2 * A <= P:
+        # per-group shares: group i gets ceil(u_i (P - A) / U) workgroups of ceil(u_i / n_i) blocks each
+        n = 0
+        for u in units:
+            if u:
+                ni = (u * (P - A) + U - 1) // U
+                cb = (u + ni - 1) // ni
+                n += G * ((u + cb - 1) // cb)
+        return n
+    c = (U + P - 1) // P
     n, s0 = 0, 0
     for u in units:
         if u:
@@ -322,8 +332,11 @@ def timeline_report(name, tau, steps, copies, anchors_cached):
     tm = np.stack(rows_m)                  # [steps, heads, 4]
     busy = tp[..., 5] > 0                  # workgroups that streamed something
     units = [0 if m[b, g] else (int(sb.seq_lens[b]) + 63) // 64 for b in range(B) for g in range(Hkv)]
-    U = sum(units)
-    c = (U + grid - 1) // grid
+    U, A = sum(units), sum(1 for u in units if u)
+    if 2 * A <= grid and U:           # per-group shares: the largest share of any group
+        c = max((u + ((u * (grid - A) + U - 1) // U) - 1) // ((u * (grid - A) + U - 1) // U) for u in units if u)
+    else:
+        c = (U + grid - 1) // grid
     steps_wave0 = (c + 3) // 4
 
     def med(x):

@@ -99,8 +99,11 @@ typedef struct sr_plan {
  *                           to 256 tokens), one workgroup per (chunk, sequence, KV group), as
  *                           the paper states it; workgroups of Sink Groups exit immediately.
  *   params->num_splits == 0 "balanced": the 64-token blocks of the Active Groups only are dealt
- *                           out in equal contiguous shares to one workgroup per compute unit
- *                           (256), so the chunk length adapts to the skip pattern.
+ *                           out to one workgroup per compute unit (256), on the device, once
+ *                           the skip decisions are known: every Active Group gets workgroups
+ *                           in proportion to its blocks (or, with more than 128 Active
+ *                           Groups, every workgroup an equal run of the blocks laid end to
+ *                           end), so the chunk length adapts to the skip pattern.
  *                           Needs B*H_kv <= 2048; larger batches fall back to fixed chunks.
  * The result does not depend on the schedule beyond fp32 rounding.
  */

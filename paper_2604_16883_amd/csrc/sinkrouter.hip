@@ -17,9 +17,11 @@
 //                      (head, workgroup).  Two schedules:
 //        balanced  (default) one workgroup per compute unit; every workgroup first obtains the
 //                  skip decisions of all groups (fused probe, or the mask of sr_probe_kernel), so
-//                  the 64-token blocks of the Active Groups only are dealt out in equal contiguous
-//                  shares.  Sink Groups cost nothing and the chip stays
-//                  full whatever the skip pattern is.
+//                  the 64-token blocks of the Active Groups only are dealt out: workgroups per
+//                  group in proportion to its blocks, one group per workgroup (or equal runs of
+//                  the blocks laid end to end when more than half as many groups are active as
+//                  there are workgroups).  Sink Groups cost nothing and the chip stays full
+//                  whatever the skip pattern is.
 //        fixed     the paper's literal Split-K: [0, L) cut into num_splits chunks, one
 //                  workgroup per (chunk, sequence, KV group); workgroups of Sink Groups
 //                  leave at once.

@@ -14,7 +14,7 @@ struct CombineArgs {
   const float* part_ml;
   const int32_t* seq_lens;
   const uint8_t* mask;
-  const int32_t* sched;   // balanced schedule, else NULL
+  const int32_t* sched;   // balanced schedule (mode, c, one pair per group), else NULL
   uint32_t* out;          // bf16 pairs
   int Hq, Hkv, G, Lmax, chunk, slots;
   int spec;               // records per wavefront requested before their number is known (1..kCombineRows)
@@ -68,26 +68,25 @@ __global__ __launch_bounds__(kCombineThreads) void sr_combine_kernel(CombineArgs
     }
   }
   // Everything the head's record count depends on is requested here, unconditionally and together with the
-  // speculative rows, as vector loads: the sequence length and the three schedule entries by lanes 0..3 of
+  // speculative rows, as vector loads: the sequence length and the four schedule entries by lanes 0..4 of
   // one load instruction (broadcast afterwards), the mask byte by another.  One memory round trip covers
   // them all; a mask test in front of the schedule loads, or scalar loads (which have to be waited for
   // one batch at a time), made it three dependent ones.
   const int bg = b * a.Hkv + g;
   const int32_t* src = a.seq_lens + b;                                       // lane 0 (and the idle lanes)
-  if (a.sched && lane >= 1 && lane <= 3) src = a.sched + (lane == 1 ? 1 : bg + lane);   // c, start[bg], start[bg + 1]
+  if (a.sched && lane >= 1 && lane <= 4) src = a.sched + (lane <= 2 ? lane - 1 : 2 * bg + lane - 1);   // mode, c, the group's pair
   const int word = *src;
   const int sink = a.mask[bg];
   const int len_raw = __builtin_amdgcn_readlane(word, 0);
-  const int c = __builtin_amdgcn_readlane(word, 1), u0 = __builtin_amdgcn_readlane(word, 2), u1 = __builtin_amdgcn_readlane(word, 3);
+  const int mode = __builtin_amdgcn_readlane(word, 1), c = __builtin_amdgcn_readlane(word, 2);
+  const int e0 = __builtin_amdgcn_readlane(word, 3), e1 = __builtin_amdgcn_readlane(word, 4);
   const int L = clamp_len(len_raw, a.Lmax);
   uint32_t* orow = a.out + (size_t)bh * (kD / 2);
   int n = 0;                                     // partial records of this head
   if (!sink && L > 0) {
-    if (a.sched) {
-      if (u1 > u0) n = (u1 - 1) / c - u0 / c + 1;
-    } else {
-      n = (L + a.chunk - 1) / a.chunk;
-    }
+    if (!a.sched) n = (L + a.chunk - 1) / a.chunk;                          // fixed chunks
+    else if (mode) n = share_records(e0, e1);                               // per-group shares: (blocks, workgroups)
+    else if (e1 > e0) n = (e1 - 1) / c - e0 / c + 1;                        // contiguous shares: units [e0, e1)
   }
   if (n == 0) {                                  // zero surrogate (Eq. 14) / empty sequence
     if (wave == 0) orow[lane] = 0u;

@@ -66,6 +66,15 @@ SR_HD uint32_t div_by(uint32_t x, uint32_t magic) {
 #endif
 }
 
+// Balanced schedule, "per-group shares" (used when at most half as many groups are active as there are workgroups):
+// with U blocks in A Active Groups and P workgroups, group i with u_i blocks gets n_i = ceil(u_i (P - A) / U) >= 1
+// workgroups (their sum is at most P), each taking ceil(u_i / n_i) consecutive blocks, so no workgroup works on two
+// groups.  share_records is the number of workgroups of a group that get any block: its partial records.
+SR_HD bool per_group_shares(int A, int P) { return A > 0 && 2 * A <= P; }
+SR_HD int share_count(int u, int U, int P, int A) { return u > 0 ? (int)(((int64_t)u * (P - A) + U - 1) / U) : 0; }
+SR_HD int share_blocks(int u, int n) { return (u + n - 1) / n; }
+SR_HD int share_records(int u, int n) { return u > 0 ? (u + share_blocks(u, n) - 1) / share_blocks(u, n) : 0; }
+
 // seq_lens[b] as the kernels use it: values outside [0, L_max] are clamped.
 SR_HD int clamp_len(int L, int Lmax) { return L < 0 ? 0 : (L > Lmax ? Lmax : L); }
 

@@ -13,7 +13,7 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
 
 // Byte offsets of the pieces of the workspace, in this order: partial outputs [heads, slots, D] fp32,
-// partial (m, l) [heads, slots, 2] fp32, group scores [NG] fp32, schedule table U, c, start[0..NG] int32,
+// partial (m, l) [heads, slots, 2] fp32, group scores [NG] fp32, schedule table (mode, c, one pair per group) int32,
 // shifted lengths [B] int32 (concentration statistics only), wall-clock stamps (timeline build only).  Every piece starts on a 256-byte boundary.
 struct Layout {
   sr_plan plan;
@@ -72,7 +72,7 @@ inline int make_layout(const sr_route_params* p, Layout* lay) {
   lay->off_ml = align_up(heads * S * kD * sizeof(float), 256);
   lay->off_score = lay->off_ml + align_up(heads * S * 2 * sizeof(float), 256);
   lay->off_sched = lay->off_score + align_up((size_t)NG * sizeof(float), 256);
-  lay->off_lens = lay->off_sched + align_up((size_t)(NG + 3) * sizeof(int32_t), 256);
+  lay->off_lens = lay->off_sched + align_up((size_t)(2 * NG + 2) * sizeof(int32_t), 256);
   lay->off_timeline = lay->off_lens + align_up((size_t)p->batch * sizeof(int32_t), 256);
   pl.workspace_bytes = lay->off_timeline + kTimelineBytes;      // no stamps in the product build
   return SR_OK;

@@ -299,10 +299,15 @@ __global__ __launch_bounds__(kThreads, 2) void sr_partial_fixed_kernel(PartialAr
   attend_range<kPaged>(a, b, g, L, t_begin, min(t_begin + a.chunk, L), s);
 }
 
-// Balanced schedule.  grid = kBalancedGrid, block = 256.  Unit = one 64-token block of an Active
-// Group; units are numbered group after group; workgroup p owns units [p*c, (p+1)*c), c = ceil(U/P).
-// Partial record j of a group belongs to workgroup (start/c + j).  Workgroup 0 leaves the schedule
-// (U, c, start[]) in `sched` for the merge kernel.
+// Balanced schedule.  grid = kBalancedGrid (P), block = 256.  Unit = one 64-token block of an Active Group.
+//   per-group shares (at most P/2 Active Groups): group i gets n_i workgroups in proportion to its blocks
+//     (share_count), each a run of share_blocks consecutive blocks: every workgroup streams one group only.  A
+//     workgroup that changes groups drains and refills its load pipeline while the rest of the chip keeps the
+//     memory queues full, which costs it 3-4 us: with contiguous shares those workgroups ended the kernel.
+//   contiguous shares (more Active Groups than that): units are numbered group after group and workgroup p
+//     owns units [p*c, (p+1)*c), c = ceil(U/P); partial record j of a group belongs to workgroup (start/c + j).
+// Workgroup 0 leaves the schedule in `sched` for the merge kernel: mode (1 = per-group), c, then per group
+// (blocks, workgroups) or (first unit, end unit).
 // With kFused every workgroup first evaluates the routing rule for all groups itself (the queries
 // and anchor rows are a few tens of KB, served by L2), as the paper's kernel does inline, so no
 // separate probe launch precedes it; workgroup 0 writes skip mask and group scores.  Otherwise
@@ -325,7 +330,7 @@ __global__ __launch_bounds__(kThreads, 2) void sr_partial_balanced_kernel(Partia
   __shared__ int start[kMaxSchedGroups + 1];
   __shared__ int lens[kMaxSchedGroups];
   __shared__ float cosv[kFused ? kMaxFusedHeads : 1];
-  __shared__ int wsum[kWaves];
+  __shared__ int wsum[2 * kWaves];
   __shared__ int first_group;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int NG = a.NG, G = a.G;
@@ -386,12 +391,34 @@ __global__ __launch_bounds__(kThreads, 2) void sr_partial_balanced_kernel(Partia
     if (kFused && p == 0 && wave == 0 && live) { a.mask[lane] = skip ? 1 : 0; if (a.group_score) a.group_score[lane] = S; }
     const int u = (live && !skip) ? (len_i + kBlock - 1) / kBlock : 0;
     const int x = wave_inclusive_scan(u);        // over the groups
-    const int start_i = x - u;
     const int U = __builtin_amdgcn_readlane(x, 63);
+    const int A = __popcll(__ballot(u > 0));
+    if (per_group_shares(A, P)) {
+      const int n = share_count(u, U, P, A);
+      const int ns = wave_inclusive_scan(n) - n;  // first workgroup of the group
+      if (p == 0 && wave == 0) {
+        if (lane == 0) { a.sched[0] = 1; a.sched[1] = 0; }
+        if (live) { a.sched[2 + 2 * lane] = u; a.sched[3 + 2 * lane] = n; }
+      }
+      SR_STAMP(a.timeline, kTimelinePartialStamps, 3);
+      const unsigned long long holds = __ballot(n > 0 && ns <= p && p < ns + n);   // at most one group
+      if (!holds) return;                         // fewer shares than workgroups
+      const int i = __ffsll(holds) - 1;
+      const int ui = __builtin_amdgcn_readlane(u, i), j = p - __builtin_amdgcn_readlane(ns, i);
+      const int cb = share_blocks(ui, __builtin_amdgcn_readlane(n, i));
+      const int blk_lo = j * cb, blk_hi = min(blk_lo + cb, ui);
+      if (blk_lo >= blk_hi) return;               // more workgroups than the group has blocks
+      const int L = __builtin_amdgcn_readlane(len_i, i);
+      const int b = i / a.Hkv, g = i - b * a.Hkv;
+      attend_range<kPaged>(a, b, g, L, blk_lo * kBlock, min(blk_hi * kBlock, L), j);
+      SR_STAMP(a.timeline, kTimelinePartialStamps, 7);
+      return;
+    }
+    const int start_i = x - u;
     const int c = (U + P - 1) / P;
     if (p == 0 && wave == 0) {
-      if (lane == 0) { a.sched[0] = U; a.sched[1] = c; a.sched[2 + NG] = U; }
-      if (live) a.sched[2 + lane] = start_i;
+      if (lane == 0) { a.sched[0] = 0; a.sched[1] = c; }
+      if (live) { a.sched[2 + 2 * lane] = start_i; a.sched[3 + 2 * lane] = x; }
     }
     const int u_lo = p * c, u_hi = min(u_lo + c, U);
     SR_STAMP(a.timeline, kTimelinePartialStamps, 3);
@@ -411,22 +438,42 @@ __global__ __launch_bounds__(kThreads, 2) void sr_partial_balanced_kernel(Partia
     SR_STAMP(a.timeline, kTimelinePartialStamps, 7);
     return;
   }
+  // More than 64 groups: the schedule is built in LDS.  Pass 1: decisions, blocks per group (a Sink Group's length
+  // is kept as -1 - L so that it counts no blocks), their total and the number of Active Groups.
+  int my_U = 0, my_A = 0;
+  for (int i = tid; i < NG; i += kThreads) {
+    bool skip;
+    if (kFused) {
+      float S = 0.f;
+      skip = a.rule.routing ? route_decide(cosv + i * G, G, lens[i], a.rule, &S) : false;
+      if (p == 0) { a.mask[i] = skip ? 1 : 0; if (a.group_score) a.group_score[i] = S; }
+    } else {
+      skip = a.mask[i] != 0;
+    }
+    if (skip) lens[i] = -1 - lens[i];
+    const int u = skip ? 0 : (lens[i] + kBlock - 1) / kBlock;
+    my_U += u;
+    my_A += u > 0;
+  }
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) { my_U += __shfl_xor(my_U, o, 64); my_A += __shfl_xor(my_A, o, 64); }
+  if (lane == 0) { wsum[wave] = my_U; wsum[kWaves + wave] = my_A; }
+  __syncthreads();
+  int U = 0, A = 0;
+#pragma unroll
+  for (int u2 = 0; u2 < kWaves; ++u2) { U += wsum[u2]; A += wsum[kWaves + u2]; }
+  const bool per_group = per_group_shares(A, P);
+  __syncthreads();                                // wsum is reused by the scan
+  // Pass 2: prefix sums of the workgroups per group (per-group shares) or of the blocks per group (contiguous).
   int carry = 0;
   for (int base = 0; base < NG; base += kThreads) {
     const int i = base + tid;
-    int u = 0;
+    int v = 0;
     if (i < NG) {
-      bool skip;
-      if (kFused) {
-        float S = 0.f;
-        skip = a.rule.routing ? route_decide(cosv + i * G, G, lens[i], a.rule, &S) : false;
-        if (p == 0) { a.mask[i] = skip ? 1 : 0; if (a.group_score) a.group_score[i] = S; }
-      } else {
-        skip = a.mask[i] != 0;
-      }
-      if (!skip) u = (lens[i] + kBlock - 1) / kBlock;
+      const int u = lens[i] > 0 ? (lens[i] + kBlock - 1) / kBlock : 0;
+      v = per_group ? share_count(u, U, P, A) : u;
     }
-    int x = u;                                   // inclusive scan inside the wavefront
+    int x = v;                                   // inclusive scan inside the wavefront
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) {
       const int y = __shfl_up(x, o, 64);
@@ -440,20 +487,38 @@ __global__ __launch_bounds__(kThreads, 2) void sr_partial_balanced_kernel(Partia
     int tot = 0;
 #pragma unroll
     for (int u2 = 0; u2 < kWaves; ++u2) tot += wsum[u2];
-    if (i < NG) start[i] = carry + woff + x - u;
+    if (i < NG) start[i] = carry + woff + x - v;
     carry += tot;
     __syncthreads();
   }
-  const int U = carry;
-  if (tid == 0) start[NG] = U;
-  const int c = (U + P - 1) / P;
+  if (tid == 0) { start[NG] = carry; first_group = -1; }
+  const int c = per_group ? 0 : (U + P - 1) / P;
   __syncthreads();
   if (p == 0) {
-    if (tid == 0) { a.sched[0] = U; a.sched[1] = c; }
-    for (int i = tid; i <= NG; i += kThreads) a.sched[2 + i] = start[i];
+    if (tid == 0) { a.sched[0] = per_group ? 1 : 0; a.sched[1] = c; }
+    for (int i = tid; i < NG; i += kThreads) {
+      const int u = lens[i] > 0 ? (lens[i] + kBlock - 1) / kBlock : 0;
+      a.sched[2 + 2 * i] = per_group ? u : start[i];
+      a.sched[3 + 2 * i] = per_group ? start[i + 1] - start[i] : start[i + 1];
+    }
+  }
+  SR_STAMP(a.timeline, kTimelinePartialStamps, 3);
+  if (per_group) {
+    for (int i = tid; i < NG; i += kThreads)
+      if (start[i] <= p && p < start[i + 1]) first_group = i;        // at most one group
+    __syncthreads();
+    const int i = first_group;
+    if (i < 0) return;                            // fewer shares than workgroups
+    const int L = lens[i], ui = (L + kBlock - 1) / kBlock, j = p - start[i];
+    const int cb = share_blocks(ui, start[i + 1] - start[i]);
+    const int blk_lo = j * cb, blk_hi = min(blk_lo + cb, ui);
+    if (blk_lo >= blk_hi) return;                 // more workgroups than the group has blocks
+    const int b = i / a.Hkv, g = i - b * a.Hkv;
+    attend_range<kPaged>(a, b, g, L, blk_lo * kBlock, min(blk_hi * kBlock, L), j);
+    SR_STAMP(a.timeline, kTimelinePartialStamps, 7);
+    return;
   }
   const int u_lo = p * c, u_hi = min(u_lo + c, U);
-  SR_STAMP(a.timeline, kTimelinePartialStamps, 3);
   if (u_lo >= u_hi) return;
   for (int i = tid; i < NG; i += kThreads)
     if (start[i] <= u_lo && u_lo < start[i + 1]) first_group = i;   // exactly one group holds u_lo

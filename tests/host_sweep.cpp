@@ -61,7 +61,7 @@ static void check_valid(const sr_route_params& p) {
   const u128 off_ml = up256((u128)heads * S * 128 * 4);
   const u128 off_score = off_ml + up256((u128)heads * S * 2 * 4);
   const u128 off_sched = off_score + up256((u128)NG * 4);
-  const u128 off_lens = off_sched + up256((u128)(NG + 3) * 4);
+  const u128 off_lens = off_sched + up256((u128)(2 * NG + 2) * 4);
   const u128 total = off_lens + up256((u128)p.batch * 4);
   CHECK(total <= (u128)SIZE_MAX);
   CHECK(lay.off_o == 0 && (u128)lay.off_ml == off_ml && (u128)lay.off_score == off_score);
@@ -132,6 +132,39 @@ static void check_pages() {
     const uint32_t top = (uint32_t)(((uint64_t)1 << 32) / d);
     for (uint32_t x = 0; x < 70000u && x < top; ++x) CHECK(div_by(x, m) == x / d);
     for (uint32_t x = top > 5000u ? top - 5000u : 0u; x < top; ++x) CHECK(div_by(x, m) == x / d);
+  }
+  // per-group shares: every group gets at least one workgroup, the workgroups suffice, the shares cover the blocks
+  {
+    const int P = kBalancedGrid;
+    unsigned seed = 12345;
+    for (int round = 0; round < 4000; ++round) {
+      seed = seed * 1664525u + 1013904223u;
+      const int A = 1 + (int)((seed >> 8) % (P / 2));
+      std::vector<int> u(A);
+      long long U = 0;
+      for (int i = 0; i < A; ++i) {
+        seed = seed * 1664525u + 1013904223u;
+        const int kind = (seed >> 28) & 3;
+        u[i] = kind == 0 ? 1 : kind == 1 ? 1 + (int)((seed >> 4) % 7) : kind == 2 ? 1 + (int)((seed >> 4) % 4096) : 1 + (int)((seed >> 4) % (1 << 18));
+        U += u[i];
+      }
+      if (U >= (1LL << 30)) continue;
+      CHECK(per_group_shares(A, P));
+      long long total = 0;
+      for (int i = 0; i < A; ++i) {
+        const int n = share_count(u[i], (int)U, P, A);
+        CHECK(n >= 1 && n <= P - A + 1);
+        const int cb = share_blocks(u[i], n), r = share_records(u[i], n);
+        CHECK(cb >= 1 && (long long)cb * n >= u[i]);                 // the shares cover the group
+        CHECK(r >= 1 && r <= n && (long long)(r - 1) * cb < u[i] && (long long)r * cb >= u[i]);
+        CHECK(r <= kBalancedGrid + 1 && r <= u[i]);                    // fits the reserved record slots
+        total += n;
+      }
+      CHECK(total <= P);
+    }
+    CHECK(!per_group_shares(0, P) && !per_group_shares(P / 2 + 1, P) && per_group_shares(P / 2, P));
+    CHECK(share_count(0, 100, P, 3) == 0 && share_records(0, 0) == 0);
+    CHECK(share_count(1 << 18, 1 << 18, P, 1) == P - 1);               // one group alone takes P - 1 workgroups
   }
   sr_paged_layout lay = {(uint32_t)sizeof(sr_paged_layout), 64, 4, 3};
   sr_route_params p = shape(1, 8, 2, 256, 0);

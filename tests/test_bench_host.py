@@ -26,10 +26,19 @@ def test_algorithmic_bytes_and_record_count_by_hand():
     mask = np.ones((4, 8), np.uint8)
     mask[0, 0] = mask[2, 5] = 0                    # two Active Groups of 512 blocks each
     plan = B.sinkrouter_plan(B.make_route_params(4, 32, 8, 32768))
-    # 1024 blocks over 256 workgroups: 4 blocks per share, 128 shares per group, 4 heads per group
-    assert bench.partial_records(w, lens, mask, plan) == 2 * 4 * 128
-    expect = 2 * 32768 * 512 + 2 * 4 * 256 + 2 * 4 * 128 * 520 + 32
+    # per-group shares: 2 groups of 512 blocks share 254 workgroups, 127 each, 5 blocks per share: 103 shares
+    # of a group get blocks; 4 heads per group
+    assert bench.partial_records(w, lens, mask, plan) == 2 * 4 * 103
+    expect = 2 * 32768 * 512 + 2 * 4 * 256 + 2 * 4 * 103 * 520 + 32
     assert bench.algorithmic_bytes(w, lens, mask, plan) == expect
+    # more than half as many Active Groups as workgroups: contiguous shares (here B = 40: 160 groups of 512 blocks,
+    # 320 blocks per workgroup, so every group's records are the 2 or 3 workgroups its units fall into)
+    w2 = synth.Workload("wide", 40, 16, 4, 32768, 0.5)
+    plan2 = B.sinkrouter_plan(B.make_route_params(40, 16, 4, 32768))
+    units = 512
+    c = (160 * units + 255) // 256
+    want = sum(4 * (((i + 1) * units - 1) // c - (i * units) // c + 1) for i in range(160))
+    assert bench.partial_records(w2, np.full((40,), 32768, np.int32), np.zeros((40, 4), np.uint8), plan2) == want
     # nothing active: only the mask bytes
     assert bench.algorithmic_bytes(w, lens, np.ones((4, 8), np.uint8), plan) == 32
     # fixed chunks: one record per (head, chunk that holds tokens)
