@@ -122,9 +122,17 @@ def time_steps(fn, steps, warmup):
     return (time.perf_counter() - t0) / steps * 1e6
 
 
+def auto_copies(kv_bytes):
+    """Distinct K/V copies to rotate through so that a step finds (almost) none of its rows in the 256 MB memory-side
+    cache: the rows a routed step touches (as little as a fifth of the cache at a skip ratio of 0.8), summed over the
+    rotation, are at least six times the cache.  Measured on the 128K-token batch: 38.8 us per routed step with 3 copies,
+    39.1 with 4, 40.4 with 6, 8, 12 and 16."""
+    return int(min(16, max(3, -(-6 * 256e6 // (0.2 * kv_bytes)))))
+
+
 class Case:
     """One workload resident in HBM: queries, lengths, `copies` distinct copies of K and V (rotated so that
-    no step finds its rows in the last-level cache), and the anchors a prefill would have cached."""
+    no step finds its rows in the last-level cache; 0 = auto_copies), and the anchors a prefill would have cached."""
 
     def __init__(self, name, copies, seed=None, seq_lens=None, page_tokens=0):
         import torch
@@ -132,6 +140,9 @@ class Case:
         w = synth.WORKLOADS[name]
         if seq_lens is not None:
             w = w.scaled(max(seq_lens), batch=len(seq_lens), name="%s ragged" % name)
+        if not copies:
+            lens = seq_lens if seq_lens is not None else [w.seq_len] * w.batch
+            copies = auto_copies(sum(lens) * w.n_kv_heads * D * 2 * 2)
         t0 = time.time()
         sb = synth.generate(w, seed=seed, seq_lens=seq_lens, threads=min(16, os.cpu_count() or 8))
         self.gen_s = time.time() - t0
@@ -262,7 +273,7 @@ def run_workload(name, steps, warmup, copies, verbose, num_splits=0, page_tokens
     case = Case(name, copies, seed=seed, seq_lens=seq_lens, page_tokens=page_tokens)
     res = {"workload": name, "description": case.w.description if seq_lens is None else
            "%s-shaped batch with ragged lengths %s" % (name, list(seq_lens)), "seed": case.sb.seed,
-           "gen_s": round(case.gen_s, 2), "copies": copies}
+           "gen_s": round(case.gen_s, 2), "copies": case.copies}
     kw = dict(num_splits=num_splits, use_graph=use_graph)
     modes = [("routed_tau0.55", dict(routing=True, tau=TAU, cached_anchors=False))]
     if prefill_anchors:
@@ -514,7 +525,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="c3", choices=["c0", "c1", "c2", "c3", "c4"])
     ap.add_argument("--also", default="c0,c1,c2,c4", help="comma list of further workloads to report ('' for none)")
-    ap.add_argument("--copies", type=int, default=3, help="distinct K/V copies rotated through")
+    ap.add_argument("--copies", type=int, default=0, help="distinct K/V copies rotated through (0 = enough to defeat the last-level cache)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="leave out the seed sweep and the ragged / paged batches")
     ap.add_argument("--lean", action="store_true",
@@ -552,7 +563,7 @@ def main():
     if a.timeline:
         for name in a.timeline.split(","):
             for tau in ([TAU, 0.453, 2.0] if name == "c1" else [TAU, 2.0]):
-                rep = timeline_report(name, tau, min(a.steps, 30), max(a.copies, 4), a.prefill_anchors)
+                rep = timeline_report(name, tau, min(a.steps, 30), a.copies, a.prefill_anchors)
                 print(timeline_markdown(rep, calib), flush=True)
                 print("<!-- %s -->\n" % json.dumps(rep), flush=True)
                 torch.cuda.empty_cache()
@@ -564,7 +575,7 @@ def main():
     torch.cuda.empty_cache()
     others, extras, seeds = {}, {}, []
     for name in [x for x in a.also.split(",") if x and x != a.workload]:
-        r, c2 = run_workload(name, a.steps, a.warmup, max(a.copies, 4), a.verbose, a.num_splits, a.paged, a.graph)
+        r, c2 = run_workload(name, a.steps, a.warmup, a.copies, a.verbose, a.num_splits, a.paged, a.graph)
         others[name] = r
         del c2
         torch.cuda.empty_cache()
@@ -585,11 +596,11 @@ def main():
             del c2
             torch.cuda.empty_cache()
         # one long and several short sequences, contiguous and paged: where the balanced schedule has to pay
-        r, c2 = run_workload("c1", a.steps, a.warmup, 4, a.verbose, seq_lens=RAGGED_LENS, taus=False)
+        r, c2 = run_workload("c1", a.steps, a.warmup, a.copies, a.verbose, seq_lens=RAGGED_LENS, taus=False)
         extras["c1_ragged"] = r
         del c2
         torch.cuda.empty_cache()
-        r, c2 = run_workload("c1", a.steps, a.warmup, 4, a.verbose, seq_lens=RAGGED_LENS, page_tokens=256, taus=False)
+        r, c2 = run_workload("c1", a.steps, a.warmup, a.copies, a.verbose, seq_lens=RAGGED_LENS, page_tokens=256, taus=False)
         r["description"] += ", paged (256-token pages, seeded random page order)"
         extras["c1_ragged_paged256"] = r
         del c2

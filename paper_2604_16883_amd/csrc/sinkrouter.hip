@@ -191,7 +191,11 @@ int decode_impl(const void* q, const void* k, const void* v, const int32_t* seq_
     c.chunk = lay.plan.chunk_tokens; c.slots = lay.plan.slots_per_head;
     c.timeline = SR_TIMELINE ? reinterpret_cast<long long*>(ws + lay.off_timeline) + (size_t)kBalancedGrid * kTimelinePartialStamps : nullptr;
     c.spec = combine_spec_rows(lay, p->batch * p->n_kv_heads);
-    ok = launch(sr_combine_kernel, dim3(p->batch * p->n_q_heads), dim3(kCombineThreads), st, c, ev[5], ev[6]);
+    const dim3 heads(p->batch * p->n_q_heads);
+    if (combine_waves(lay, p->batch * p->n_kv_heads) == kCombineWavesNarrow)
+      ok = launch(sr_combine_kernel<kCombineWavesNarrow>, heads, dim3(64 * kCombineWavesNarrow), st, c, ev[5], ev[6]);
+    else
+      ok = launch(sr_combine_kernel<kCombineWavesWide>, heads, dim3(64 * kCombineWavesWide), st, c, ev[5], ev[6]);
   }
   if (stage_us) {
     if (ok) ok = hipEventRecord(ev[7], st) == hipSuccess;

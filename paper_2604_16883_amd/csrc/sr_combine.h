@@ -7,7 +7,8 @@
 namespace {
 
 // ------------------------------------------------------------------------------------------
-// Merge of the partials.  grid = B*H_q, block = 1024 (16 wavefronts; lane owns 2 columns).
+// Merge of the partials.  grid = B*H_q, block = NW wavefronts (16, or 8 where heads have few records: the
+// launch of a workgroup's wavefronts is part of the step's latency).
 // ------------------------------------------------------------------------------------------
 struct CombineArgs {
   const float* part_o;
@@ -33,17 +34,16 @@ struct CombineArgs {
 };
 
 // One pass: every wavefront keeps a running (max, sum, weighted rows) over the records it owns
-// (record s belongs to wavefront s % 16, to its lower or upper half by (s / 16) % 2) and the 16
+// (record s belongs to wavefront s % NW, to its lower or upper half by (s / NW) % 2) and the NW
 // wavefronts are merged through LDS.  A half wavefront reads a whole 512-byte record row per load (32
-// lanes x 16 bytes) and holds kCombineRows of them in flight, so one sweep takes 32 kCombineRows = 128
-// records (measured: 8-byte loads per lane and 8 rows in flight cost heads with more than 128 records a
+// lanes x 16 bytes) and holds kCombineRows of them in flight, so one sweep takes 2 NW kCombineRows records (128 with 16 wavefronts) (measured: 8-byte loads per lane and 8 rows in flight cost heads with more than 128 records a
 // third round trip, 0.9 us on the 200K-context workload; 8 rows of 16-byte loads cost every launch 0.3 us).
 // The first records of every wavefront (spec of them) are requested at kernel entry, before the number
 // of records is known (it takes a load of the mask and of the schedule to know it); when spec covers the
 // head's records the merge costs one memory round trip.  What was fetched beyond the last record is
 // discarded.  The host sets spec (combine_spec_rows): more would be wasted reads.
-__global__ __launch_bounds__(kCombineThreads) void sr_combine_kernel(CombineArgs a) {
-  constexpr int NW = kCombineThreads / 64;
+template <int NW>
+__global__ __launch_bounds__(NW * 64) void sr_combine_kernel(CombineArgs a) {
   constexpr int UN = kCombineRows;
   const int bh = blockIdx.x;
 #if SR_TIMELINE

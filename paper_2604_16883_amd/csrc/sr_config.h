@@ -35,7 +35,7 @@ constexpr int kWaves = SR_WAVES;     // wavefronts per partial workgroup
 constexpr int kThreads = 64 * kWaves;
 constexpr int kMaxGroup = 16;        // query heads per KV group that fit the MFMA tile
 constexpr int kChunkUnit = kBlock * kWaves;
-constexpr int kCombineThreads = 1024;
+constexpr int kCombineWavesWide = 16, kCombineWavesNarrow = 8;   // wavefronts of a merge workgroup (see combine_waves)
 #ifndef SR_COMBINE_ROWS
 #define SR_COMBINE_ROWS 4
 #endif
@@ -71,7 +71,9 @@ SR_HD uint32_t div_by(uint32_t x, uint32_t magic) {
 // workgroups (their sum is at most P), each taking ceil(u_i / n_i) consecutive blocks, so no workgroup works on two
 // groups.  share_records is the number of workgroups of a group that get any block: its partial records.
 SR_HD bool per_group_shares(int A, int P) { return A > 0 && 2 * A <= P; }
-SR_HD int share_count(int u, int U, int P, int A) { return u > 0 ? (int)(((int64_t)u * (P - A) + U - 1) / U) : 0; }
+SR_HD int share_count(int u, int U, int P, int A) {        // u (P - A) < 2^18 * 2^8: 32-bit arithmetic is exact
+  return u > 0 ? (int)(((uint32_t)u * (uint32_t)(P - A) + (uint32_t)U - 1u) / (uint32_t)U) : 0;
+}
 SR_HD int share_blocks(int u, int n) { return (u + n - 1) / n; }
 SR_HD int share_records(int u, int n) { return u > 0 ? (u + share_blocks(u, n) - 1) / share_blocks(u, n) : 0; }
 

@@ -136,14 +136,24 @@ inline int check_paged_args(const int32_t* block_table, const sr_paged_layout* l
   return SR_OK;
 }
 
-// Rows the merge kernel requests per wavefront before it knows how many records a head has: enough for
-// a head when every group is active (shares / groups + 1 records in the balanced schedule).  A larger guess
-// (sized for the paper's retained budget of about 40 % of the groups) measured no faster: every head requests
-// these rows, Sink Groups' heads included.
+// Records a head has when every group is active: shares / groups + 1 in the balanced schedule, else the chunks.
+inline int expected_records(const Layout& lay, int NG) {
+  return lay.plan.schedule == 1 ? kBalancedGrid / NG + 1 : lay.plan.num_splits;
+}
+
+// Wavefronts of a merge workgroup: 16, or 8 where heads are expected to have at most 16 records (more than 16
+// groups share the 256 workgroups).  Launching 8 wavefronts instead of 16 takes the 128K-token batch's step from 39.6
+// to 39.0 us; with 8 everywhere, heads with hundreds of records (few Active Groups) need more sweeps (+0.2 us).
+inline int combine_waves(const Layout& lay, int NG) {
+  return expected_records(lay, NG) <= 16 ? kCombineWavesNarrow : kCombineWavesWide;
+}
+
+// Rows the merge kernel requests per half wavefront before it knows how many records a head has: enough for
+// a head when every group is active.  A larger guess (sized for the paper's retained budget of about 40 % of
+// the groups) measured no faster: every head requests these rows, Sink Groups' heads included.
 inline int combine_spec_rows(const Layout& lay, int NG) {
-  const int expect = lay.plan.schedule == 1 ? kBalancedGrid / NG + 1 : lay.plan.num_splits;
-  const int per_row = 2 * (kCombineThreads / 64);     // one load instruction of the 16 wavefronts covers 32 records
-  const int rows = (expect + per_row - 1) / per_row;
+  const int per_row = 2 * combine_waves(lay, NG);     // one load instruction of the workgroup covers this many records
+  const int rows = (expected_records(lay, NG) + per_row - 1) / per_row;
   return rows < 1 ? 1 : (rows > kCombineRows ? kCombineRows : rows);
 }
 
