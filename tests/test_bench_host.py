@@ -99,3 +99,47 @@ def test_result_tables_render():
             "cpu_baseline": None}
     md = bench.results_markdown(line)
     assert "| c3 | 0.750 | 500.0 MB | 80.0 | 6250 | 78.0 % | 88.0 |" in md and "n/a" in md and "| 3000 |" in md
+
+
+def test_profile_summary_end_to_end_on_synthetic_rocprof_output(tmp_path, monkeypatch):
+    """The summariser on a hand-made set of rocprofv3 csv files: dispatches attributed to modes by the plan, counter
+    units scaled by the copy kernel, warm-up dispatches left out, summary and counter record written."""
+    base = tmp_path / "prof_cX"
+    for d in ("trace", "fetch", "write"):
+        (base / d).mkdir(parents=True)
+    plan = [["routed_tau0.55", 3], ["dense", 2]]
+    line = {"metric": "m", "steps": 1, "warmup": 1,
+            "detail": {"cX": {"description": "test shape", "dispatch_plan": plan,
+                              "routed_tau0.55": {"skip_ratio": 0.5, "algorithmic_bytes": 2048000},
+                              "dense": {"skip_ratio": 0.0, "algorithmic_bytes": 4096000}}}}
+    (base / "trace.log").write_text("noise\n" + json.dumps(line) + "\n")
+    part, comb = "void sr_partial_balanced_kernel<true, false>(PartialArgs)", "void sr_combine_kernel<16>(CombineArgs)"
+    rows, t = [], 1000
+    durs = [9000, 2000, 2200, 4000, 4400]                       # ns; the first of each mode is warm-up
+    for d in durs:
+        rows.append((part, t, t + d)); t += d + 1500
+        rows.append((comb, t, t + 3000)); t += 3000 + 1200
+    with open(base / "trace" / "t_kernel_trace.csv", "w") as f:
+        f.write("Kernel_Name,Start_Timestamp,End_Timestamp\n")
+        for n, a, b in rows:
+            f.write('"%s",%d,%d\n' % (n, a, b))
+    with open(base / "trace" / "t_kernel_stats.csv", "w") as f:
+        f.write("Name,Calls,AverageNs,MinNs,MaxNs\n")
+        f.write('"%s",5,4320,2000,9000\n"%s",5,3000,3000,3000\n' % (part, comb))
+    for d, name, copy_units, unit in (("fetch", "f", 524288, 2048), ("write", "w", 1048576, 1024)):
+        with open(base / d / (name + "_counter_collection.csv"), "w") as f:
+            f.write("Kernel_Name,Counter_Value\n")
+            f.write('"sr_copy_probe_kernel(uint4*, uint4 const*, unsigned long)",%d\n' % copy_units)
+            for i, _ in enumerate(durs):
+                bytes_ = (2048000 if i < 3 else 4096000) if d == "fetch" else 10240
+                f.write('"%s",%d\n"%s",%d\n' % (part, bytes_ // unit, comb, 1))
+    monkeypatch.setattr(profile_summary, "ROOT", str(tmp_path))
+    profile_summary.main(["x", str(base), "cX"])
+    rec = json.load(open(tmp_path / "profiles" / "traffic.json"))["cX"]
+    r = rec["routed_tau0.55"]
+    assert r["fetch_bytes"] == 2048000 and r["write_bytes"] == 10240 and r["trace_us_mean"] == 2.1 and r["trace_us_min"] == 2.0
+    assert rec["dense"]["fetch_bytes"] == 4096000 and rec["dense"]["trace_us_mean"] == 4.4
+    assert r["kernel_source_sha"] == bench.kernel_source_sha() and r["fetch_unit_bytes"] == 2048.0
+    md = open(tmp_path / "profiles" / "sr_partial_balanced_kernel_cX.md").read()
+    assert "| routed_tau0.55 | 0.500 | 2.1 / 2.0 | 2.05 | 2.05 | 0.01 | 1.0050 |" in md and "rocprofv3 --pmc FETCH_SIZE" in md
+    assert "| 3.0 | 1.50 |" in md                                 # merge kernel duration and the gap behind the partial kernel
