@@ -393,48 +393,25 @@ __global__ __launch_bounds__(kThreads, 2) void sr_partial_balanced_kernel(Partia
     const int x = wave_inclusive_scan(u);        // over the groups
     const int U = __builtin_amdgcn_readlane(x, 63);
     const int A = __popcll(__ballot(u > 0));
-    if (per_group_shares(A, P)) {
-      const int n = share_count(u, U, P, A);
-      const int ns = wave_inclusive_scan(n) - n;  // first workgroup of the group
-      if (p == 0 && wave == 0) {
-        if (lane == 0) { a.sched[0] = 1; a.sched[1] = 0; }
-        if (live) { a.sched[2 + 2 * lane] = u; a.sched[3 + 2 * lane] = n; }
-      }
-      SR_STAMP(a.timeline, kTimelinePartialStamps, 3);
-      const unsigned long long holds = __ballot(n > 0 && ns <= p && p < ns + n);   // at most one group
-      if (!holds) return;                         // fewer shares than workgroups
-      const int i = __ffsll(holds) - 1;
-      const int ui = __builtin_amdgcn_readlane(u, i), j = p - __builtin_amdgcn_readlane(ns, i);
-      const int cb = share_blocks(ui, __builtin_amdgcn_readlane(n, i));
-      const int blk_lo = j * cb, blk_hi = min(blk_lo + cb, ui);
-      if (blk_lo >= blk_hi) return;               // more workgroups than the group has blocks
-      const int L = __builtin_amdgcn_readlane(len_i, i);
-      const int b = i / a.Hkv, g = i - b * a.Hkv;
-      attend_range<kPaged>(a, b, g, L, blk_lo * kBlock, min(blk_hi * kBlock, L), j);
-      SR_STAMP(a.timeline, kTimelinePartialStamps, 7);
-      return;
-    }
-    const int start_i = x - u;
-    const int c = (U + P - 1) / P;
+    // at most 64 Active Groups, fewer than half the workgroups: always per-group shares
+    static_assert(2 * 64 <= kBalancedGrid, "the register-built schedule relies on per-group shares");
+    const int n = share_count(u, U, P, A);
+    const int ns = wave_inclusive_scan(n) - n;    // first workgroup of the group
     if (p == 0 && wave == 0) {
-      if (lane == 0) { a.sched[0] = 0; a.sched[1] = c; }
-      if (live) { a.sched[2 + 2 * lane] = start_i; a.sched[3 + 2 * lane] = x; }
+      if (lane == 0) { a.sched[0] = 1; a.sched[1] = 0; }
+      if (live) { a.sched[2 + 2 * lane] = u; a.sched[3 + 2 * lane] = n; }
     }
-    const int u_lo = p * c, u_hi = min(u_lo + c, U);
     SR_STAMP(a.timeline, kTimelinePartialStamps, 3);
-    if (u_lo >= u_hi) return;
-    const unsigned long long holds = __ballot(u > 0 && start_i <= u_lo && u_lo < start_i + u);   // exactly one group
-    for (int i = __ffsll(holds) - 1; i < NG; ++i) {
-      const int s0 = __builtin_amdgcn_readlane(start_i, i);
-      if (s0 >= u_hi) break;
-      const int un = __builtin_amdgcn_readlane(u, i);
-      if (un == 0) continue;                      // Sink Group or empty sequence
-      const int L = __builtin_amdgcn_readlane(len_i, i);
-      const int b = i / a.Hkv, g = i - b * a.Hkv;
-      const int blk_lo = max(u_lo, s0) - s0, blk_hi = min(u_hi, s0 + un) - s0;
-      attend_range<kPaged>(a, b, g, L, blk_lo * kBlock, min(blk_hi * kBlock, L), p - s0 / c);
-      __syncthreads();                            // LDS of attend_range is reused by the next segment
-    }
+    const unsigned long long holds = __ballot(n > 0 && ns <= p && p < ns + n);   // at most one group
+    if (!holds) return;                           // fewer shares than workgroups, or nothing active
+    const int i = __ffsll(holds) - 1;
+    const int ui = __builtin_amdgcn_readlane(u, i), j = p - __builtin_amdgcn_readlane(ns, i);
+    const int cb = share_blocks(ui, __builtin_amdgcn_readlane(n, i));
+    const int blk_lo = j * cb, blk_hi = min(blk_lo + cb, ui);
+    if (blk_lo >= blk_hi) return;                 // more workgroups than the group has blocks
+    const int L = __builtin_amdgcn_readlane(len_i, i);
+    const int b = div_by(i, a.hkv_magic), g = i - b * a.Hkv;
+    attend_range<kPaged>(a, b, g, L, blk_lo * kBlock, min(blk_hi * kBlock, L), j);
     SR_STAMP(a.timeline, kTimelinePartialStamps, 7);
     return;
   }
