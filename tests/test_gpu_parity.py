@@ -96,6 +96,25 @@ def test_large_batches_take_the_unfused_and_fixed_paths():
     assert 0 < rep["skip_ratio"] < 1
 
 
+@pytest.mark.parametrize("empty", [0, 1, 2], ids=["130-active", "128-active", "126-active"])
+def test_both_sides_of_the_share_scheme_switch(empty):
+    """130 (sequence, group) pairs, routing off, `empty` sequences of length 0: 130 Active Groups take contiguous
+    shares (more than half as many as workgroups), 128 and 126 take per-group shares, built in LDS (more than 64
+    groups).  Ragged lengths, so the groups get different numbers of workgroups."""
+    B, Hq, Hkv, L = 65, 4, 2, 700
+    lens = [L - 9 * (b % 23) for b in range(B)]
+    for b in range(empty):
+        lens[7 + 11 * b] = 0
+    w = synth.Workload("switch", B, Hq, Hkv, L, 0.5, base_seed=300 + empty, planted_per_head=4)
+    sb = synth.generate(w, seq_lens=lens)
+    for kw in (dict(routing_enabled=False), dict(tau_coef=(0, 0, 0, 0.55))):
+        res = gu.run_hip(sb.q, sb.k, sb.v, sb.seq_lens, **kw)
+        ref = oracle.decode(sb.q, sb.k, sb.v, sb.seq_lens, want_dense=True, **kw)
+        rep = gu.compare(res, ref, w.group_size, "switch %d %s" % (empty, kw))
+        print("switch", empty, kw, rep, flush=True)
+        assert res["plan"].schedule == 1
+
+
 def test_edge_lengths():
     # lengths 0 and 1, exactly one block, one block + 1, all with a poisoned tail beyond seq_len
     w = synth.Workload("edge", 6, 8, 2, 300, 0.5, base_seed=77)
