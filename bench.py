@@ -334,7 +334,11 @@ def timeline_report(name, tau, steps, copies, anchors_cached):
         if s % 4 == 0:
             ev_us.append(case.call(p, s + 1, profiled=True))
         tp = t[:grid * 8].reshape(grid, 8)
-        tm = t[grid * 8:].reshape(-1, 4)[:B * Hq]
+        tm = t[grid * 8:].reshape(-1, 4)
+        # a head's merge may be split over several workgroups (column parts): entry = first of them, the rest = last
+        parts = max(int((tm[:, 0] > 0).sum()) // (B * Hq), 1)
+        tm = tm[:B * Hq * parts].reshape(B * Hq, parts, 4)
+        tm = np.concatenate([tm[..., :1].min(axis=1), tm[..., 1:].max(axis=1)], axis=1)
         t0 = tp[:, 0].min()
         rows_p.append(tp - t0)
         rows_m.append(tm - t0)

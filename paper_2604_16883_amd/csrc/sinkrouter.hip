@@ -190,12 +190,13 @@ int decode_impl(const void* q, const void* k, const void* v, const int32_t* seq_
     c.Hq = p->n_q_heads; c.Hkv = p->n_kv_heads; c.G = lay.plan.group_size; c.Lmax = p->max_seq_len;
     c.chunk = lay.plan.chunk_tokens; c.slots = lay.plan.slots_per_head;
     c.timeline = SR_TIMELINE ? reinterpret_cast<long long*>(ws + lay.off_timeline) + (size_t)kBalancedGrid * kTimelinePartialStamps : nullptr;
-    c.spec = combine_spec_rows(lay, p->batch * p->n_kv_heads);
-    const dim3 heads(p->batch * p->n_q_heads);
-    if (combine_waves(lay, p->batch * p->n_kv_heads) == kCombineWavesNarrow)
-      ok = launch(sr_combine_kernel<kCombineWavesNarrow>, heads, dim3(64 * kCombineWavesNarrow), st, c, ev[5], ev[6]);
+    const int NG = p->batch * p->n_kv_heads;
+    c.spec = combine_spec_records(lay, NG);
+    const dim3 groups((unsigned)(p->batch * p->n_q_heads * combine_parts(lay, NG)));
+    if (combine_narrow(lay, NG))
+      ok = launch(sr_combine_kernel<kCombineWavesNarrow, kCombinePartsNarrow, kCombineRowsNarrow>, groups, dim3(64 * kCombineWavesNarrow), st, c, ev[5], ev[6]);
     else
-      ok = launch(sr_combine_kernel<kCombineWavesWide>, heads, dim3(64 * kCombineWavesWide), st, c, ev[5], ev[6]);
+      ok = launch(sr_combine_kernel<kCombineWavesWide, kCombinePartsWide, kCombineRowsWide>, groups, dim3(64 * kCombineWavesWide), st, c, ev[5], ev[6]);
   }
   if (stage_us) {
     if (ok) ok = hipEventRecord(ev[7], st) == hipSuccess;

@@ -35,11 +35,14 @@ constexpr int kWaves = SR_WAVES;     // wavefronts per partial workgroup
 constexpr int kThreads = 64 * kWaves;
 constexpr int kMaxGroup = 16;        // query heads per KV group that fit the MFMA tile
 constexpr int kChunkUnit = kBlock * kWaves;
-constexpr int kCombineWavesWide = 16, kCombineWavesNarrow = 8;   // wavefronts of a merge workgroup (see combine_waves)
-#ifndef SR_COMBINE_ROWS
-#define SR_COMBINE_ROWS 4
-#endif
-constexpr int kCombineRows = SR_COMBINE_ROWS;   // record rows a half wavefront of the merge keeps in flight
+// Merge workgroups come in two shapes (see combine_narrow).  Few records per head: 8 wavefronts on a head's whole
+// row, 4 record rows in flight (64 records per sweep).  Many records per head: a head is split into 8 column parts,
+// one workgroup of 4 wavefronts each, 4 rows in flight (256 records per sweep, all a head can have in the balanced
+// schedule).  Measured on the 200K- and 512K-token workloads: 16 wavefronts x 4 parts x 2 rows +0.2 / +0.4 us per step,
+// 8 x 4 x 4 and 8 x 8 x 2 within 0.1 us, 16 x 8 x 1 +0.3 / +1.2 us, 16 wavefronts on whole rows (8 rows in flight) +1.3 / +1.0 us.
+constexpr int kCombineWavesWide = 4, kCombineWavesNarrow = 8;
+constexpr int kCombinePartsWide = 8, kCombinePartsNarrow = 1;
+constexpr int kCombineRowsWide = 4, kCombineRowsNarrow = 4;
 constexpr int kBalancedGrid = SR_GRID;   // persistent workgroups of the balanced schedule: one per compute unit
 constexpr int kMaxSchedGroups = 2048;  // (sequence, KV group) pairs the balanced schedule scans in LDS
 constexpr int kMaxFusedHeads = 512;    // query heads (all sequences) the balanced kernel probes itself

@@ -141,20 +141,39 @@ inline int expected_records(const Layout& lay, int NG) {
   return lay.plan.schedule == 1 ? kBalancedGrid / NG + 1 : lay.plan.num_splits;
 }
 
-// Wavefronts of a merge workgroup: 16, or 8 where heads are expected to have at most 16 records (more than 16
-// groups share the 256 workgroups).  Launching 8 wavefronts instead of 16 shortens the 128K-token batch's step by
-// 0.5 us; with 8 everywhere, heads with hundreds of records (few Active Groups) need more sweeps (+0.2 us).
-inline int combine_waves(const Layout& lay, int NG) {
-  return expected_records(lay, NG) <= 16 ? kCombineWavesNarrow : kCombineWavesWide;
+// Shape of the merge workgroups.  Narrow (8 wavefronts on a head's whole row) where heads are expected to have at
+// most 16 records (more than 16 groups share the 256 workgroups); else a head is split into column parts of 4
+// wavefronts each: with few Active Groups a head has hundreds of records and only a few heads have any, and one
+// compute unit per head takes longer to pull a head's 130 KB of records than a memory round trip (200K-token
+// workload: 8 busy heads, -1.1 us per step with the split).  The narrow shape on the 128K-token batch: 4 wavefronts
+// x 2 or 4 parts +0.1-0.2 us, 2 wavefronts x 4 or 8 parts +0.3-0.4 us.
+inline bool combine_narrow(const Layout& lay, int NG) { return expected_records(lay, NG) <= 16; }
+inline int combine_waves(const Layout& lay, int NG) { return combine_narrow(lay, NG) ? kCombineWavesNarrow : kCombineWavesWide; }
+
+// Column parts a head's merge is split into (workgroups per head): 1 for the narrow shape, kCombinePartsWide else.
+inline int combine_parts(const Layout& lay, int NG) {
+  return combine_narrow(lay, NG) ? kCombinePartsNarrow : kCombinePartsWide;
 }
 
-// Rows the merge kernel requests per half wavefront before it knows how many records a head has: enough for
-// a head when every group is active.  A larger guess (sized for the paper's retained budget of about 40 % of
-// the groups) measured no faster: every head requests these rows, Sink Groups' heads included.
-inline int combine_spec_rows(const Layout& lay, int NG) {
-  const int per_row = 2 * combine_waves(lay, NG);     // one load instruction of the workgroup covers this many records
-  const int rows = (expected_records(lay, NG) + per_row - 1) / per_row;
-  return rows < 1 ? 1 : (rows > kCombineRows ? kCombineRows : rows);
+// Records of a head the merge kernel requests before it knows how many the head has: enough for a head when every
+// group is active (narrow shape: rounded up to what one load instruction of the workgroup covers), at most one
+// sweep and never more than the slots a head has.  Every head requests them, Sink Groups' heads included; what is
+// not a record is dropped.  Four times as many (a head covered down to a quarter of the groups being active) measured
+// the same on the 200K- and 512K-token workloads: the second request follows the first by much less than a cold
+// round trip.
+inline int combine_spec_records(const Layout& lay, int NG) {
+  const int e = expected_records(lay, NG);
+  int spec;
+  if (combine_narrow(lay, NG)) {
+    const int per_row = 2 * kCombinePartsNarrow * kCombineWavesNarrow;
+    spec = (e + per_row - 1) / per_row * per_row;
+    if (spec > per_row * kCombineRowsNarrow) spec = per_row * kCombineRowsNarrow;
+  } else {
+    const int sweep = kCombineWavesWide * 2 * kCombinePartsWide * kCombineRowsWide;   // 64 / (32 / parts) records per load
+    spec = e > sweep ? sweep : e;
+  }
+  if (spec > lay.plan.slots_per_head) spec = lay.plan.slots_per_head;
+  return spec < 1 ? 1 : spec;
 }
 
 }  // namespace

@@ -69,9 +69,12 @@ static void check_valid(const sr_route_params& p) {
   CHECK(lay.off_o < lay.off_ml && lay.off_ml < lay.off_score && lay.off_score < lay.off_sched);
   CHECK(lay.off_sched < lay.off_lens && lay.off_lens < pl.workspace_bytes);
   CHECK(lay.off_ml % 256 == 0 && lay.off_score % 256 == 0 && lay.off_sched % 256 == 0 && lay.off_lens % 256 == 0);
-  const int spec = combine_spec_rows(lay, (int)NG), cw = combine_waves(lay, (int)NG);
-  CHECK(spec >= 1 && spec <= kCombineRows && (cw == 8 || cw == 16));
-  CHECK(cw == 16 || expected_records(lay, (int)NG) <= 16);
+  const int spec = combine_spec_records(lay, (int)NG), cw = combine_waves(lay, (int)NG), parts = combine_parts(lay, (int)NG);
+  CHECK(spec >= 1 && spec <= pl.slots_per_head && (cw == kCombineWavesNarrow || cw == kCombineWavesWide) &&
+        parts == (combine_narrow(lay, (int)NG) ? kCombinePartsNarrow : kCombinePartsWide));
+  CHECK(spec <= 2 * cw * parts * (combine_narrow(lay, (int)NG) ? kCombineRowsNarrow : kCombineRowsWide));   // one sweep at most
+  CHECK((int64_t)p.batch * p.n_q_heads * parts <= INT32_MAX);                                       // the merge grid
+  CHECK(!combine_narrow(lay, (int)NG) || expected_records(lay, (int)NG) <= 16);
   // the whole argument check on fake, suitably aligned addresses
   sr_route_params q = p;
   q.workspace = (void*)0x7000000;

@@ -115,6 +115,33 @@ def test_both_sides_of_the_share_scheme_switch(empty):
         assert res["plan"].schedule == 1
 
 
+@pytest.mark.parametrize("shape", ["narrow", "wide-fixed", "wide-balanced"])
+def test_heads_with_more_records_than_one_merge_sweep(shape):
+    """The merge kernel takes a head's records in sweeps (64 records with the narrow workgroup shape, 256 with the
+    wide one, whose four column parts of a head must also line up).  narrow: 18 (sequence, group) pairs of which one
+    sequence's two are non-empty, so each gets 127 of the 256 workgroups, which take 2 blocks each: 100 records per
+    head, two sweeps.
+    wide-fixed: 300 fixed chunks of 256 tokens, one group: two sweeps.  wide-balanced: one group on all 256 shares."""
+    if shape == "narrow":
+        B, Hq, Hkv, L = 9, 8, 2, 64 * 200
+        lens = [0] * B
+        lens[4] = L - 5
+        kw, records = dict(), 100
+    elif shape == "wide-fixed":
+        B, Hq, Hkv, L = 1, 4, 1, 256 * 300
+        lens, kw, records = [L - 3], dict(num_splits=300), 300
+    else:
+        B, Hq, Hkv, L = 1, 4, 1, 64 * 700
+        lens, kw, records = [L - 70], dict(), 233     # 699 blocks over 255 workgroups: shares of 3 blocks
+    w = synth.Workload("sweeps", B, Hq, Hkv, L, 0.5, base_seed=410, planted_per_head=4)
+    sb = synth.generate(w, seq_lens=lens)
+    res = gu.run_hip(sb.q, sb.k, sb.v, sb.seq_lens, routing_enabled=False, **kw)
+    ref = oracle.decode(sb.q, sb.k, sb.v, sb.seq_lens, want_dense=True, routing_enabled=False)
+    rep = gu.compare(res, ref, w.group_size, "sweeps " + shape)
+    print("sweeps", shape, rep, res["plan"].schedule, res["plan"].slots_per_head, flush=True)
+    assert res["plan"].slots_per_head >= records
+
+
 def test_edge_lengths():
     # lengths 0 and 1, exactly one block, one block + 1, all with a poisoned tail beyond seq_len
     w = synth.Workload("edge", 6, 8, 2, 300, 0.5, base_seed=77)
