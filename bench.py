@@ -37,6 +37,7 @@ TRAFFIC_JSON = os.path.join(ROOT, "profiles", "traffic.json")
 # sources that decide what the partial kernel reads and writes: a counter record is valid for these only
 KERNEL_SOURCES = ["sr_config.h", "sr_common.h", "sr_route.h", "sr_partial.h"]
 RAGGED_LENS = [32768, 20011, 4097, 65]      # c1-shaped batch with one long and several short sequences
+CONTEXT_SWEEP = [8192, 16384, 32768, 65536, 131072, 262144]   # c3-shaped layer at shorter contexts (512K is the headline)
 
 
 def kernel_source_sha() -> str:
@@ -122,12 +123,25 @@ def time_steps(fn, steps, warmup):
     return (time.perf_counter() - t0) / steps * 1e6
 
 
+def settle():
+    """Frees the cached device memory and waits for the device to get over it.  For some hundred milliseconds after
+    gigabytes of device memory are released every kernel streams 3-4 % slower (the 128K-token step: 41.7 instead of
+    40.2 us for at least 140 ms after an 8 GiB buffer is freed, back to 40.2 us a second later; allocating has no
+    such effect), so a workload timed right after its predecessor's buffers were freed would be charged for that."""
+    import torch
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    time.sleep(1.5)
+
+
 def auto_copies(kv_bytes):
     """Distinct K/V copies to rotate through so that a step finds (almost) none of its rows in the 256 MB memory-side
     cache: the rows a routed step touches (as little as a fifth of the cache at a skip ratio of 0.8), summed over the
     rotation, are at least six times the cache.  Measured on the 128K-token batch: 38.8 us per routed step with 3 copies,
-    39.1 with 4, 40.4 with 6, 8, 12 and 16."""
-    return int(min(16, max(3, -(-6 * 256e6 // (0.2 * kv_bytes)))))
+    39.1 with 4, 40.4 with 6, 8, 12 and 16.  Short contexts need hundreds of copies (a 4K-token cache is 17 MB); the
+    rotation is capped at 512 copies and 32 GB."""
+    want = -(-6 * 256e6 // (0.2 * kv_bytes))
+    return int(max(3, min(want, 512, 32e9 // kv_bytes)))
 
 
 class Case:
@@ -162,8 +176,16 @@ class Case:
         else:
             k0 = torch.from_numpy(sb.k.view(np.int16)).cuda()
             v0 = torch.from_numpy(sb.v.view(np.int16)).cuda()
-        self.ks = [k0] + [k0.clone() for _ in range(copies - 1)]
-        self.vs = [v0] + [v0.clone() for _ in range(copies - 1)]
+        # all copies of K in one allocation and all copies of V in another, as the layers of a model's cache would be:
+        # hundreds of separate small buffers, freed again, leave the device memory fragmented for whatever is allocated
+        # next (measured: the 128K-token batch then runs 3-4 % slower for the rest of the process)
+        k_all = torch.empty((copies,) + tuple(k0.shape), dtype=k0.dtype, device="cuda")
+        v_all = torch.empty((copies,) + tuple(v0.shape), dtype=v0.dtype, device="cuda")
+        k_all[:] = k0
+        v_all[:] = v0
+        del k0, v0
+        self.ks = [k_all[i] for i in range(copies)]
+        self.vs = [v_all[i] for i in range(copies)]
         self.out = torch.empty((self.B, self.Hq, D), dtype=torch.int16, device="cuda")
         self.mask = torch.empty((self.B, self.Hkv), dtype=torch.uint8, device="cuda")
         # prefill-side anchor caching (Section 4.1): K_0 and its norm are extracted once per sequence, by the
@@ -469,6 +491,21 @@ def results_markdown(line):
         for s in line["seeds"]:
             out.append("| %d | %.3f | %.1f MB | %.1f | %.1f %% | %.1f %% |" % (s["seed"], s["skip_ratio"], s["algorithmic_bytes"] / 1e6, s["us_per_step"],
                                                                        100 * s["step_frac_of_peak"], 100 * s["partial_frac_of_peak"]))
+    pts = (line.get("context_sweep") or {}).get("points") or []
+    if pts:
+        main = det.get("c3")
+        out += ["", "Step time against context length, c3-shaped layer (B1, 64 query / 8 KV heads), routed at tau = 0.55 and dense on identical "
+                "inputs (Section 5.3 of the paper reports small gains below 64K tokens, growing with the context):", "",
+                "| context | skip | K/V copies rotated | routed step us | of 8 TB/s | dense step us | of 8 TB/s | speed-up |", "|---|---|---|---|---|---|---|---|"]
+        for s in pts:
+            out.append("| %d | %.3f | %d | %.1f | %.1f %% | %.1f | %.1f %% | %.2fx |" % (
+                s["context"], s["skip_ratio"], s["copies"], s["us_per_step"], 100 * s["step_frac_of_peak"], s["dense_us_per_step"],
+                100 * s["dense_step_frac_of_peak"], s["routed_vs_dense_speedup"]))
+        if main:
+            rt, dn = main["routed_tau0.55"], main["dense"]
+            out.append("| 524288 | %.3f | %d | %.1f | %.1f %% | %.1f | %.1f %% | %.2fx |" % (
+                rt["skip_ratio"], main["copies"], rt["us_per_step"], 100 * rt["step_frac_of_peak"], dn["us_per_step"],
+                100 * dn["step_frac_of_peak"], main["routed_vs_dense_speedup"]))
     rf, cpu = line["roofline"], line["cpu_baseline"]
     out += ["", "Streaming-read probe of the same run: %.0f GB/s.  HBM traffic of the partial kernel from hardware counters: %s "
             "(%s)." % (rf["stream_read_probe_GBps"], "%.1f MB = %.4f x the algorithmic bytes" % (rf["traffic"] / 1e6, rf["traffic_ratio"])
@@ -570,19 +607,19 @@ def main():
                 rep = timeline_report(name, tau, min(a.steps, 30), a.copies, a.prefill_anchors)
                 print(timeline_markdown(rep, calib), flush=True)
                 print("<!-- %s -->\n" % json.dumps(rep), flush=True)
-                torch.cuda.empty_cache()
+                settle()
         return
 
     main_res, case = run_workload(a.workload, a.steps, a.warmup, a.copies, a.verbose, a.num_splits, a.paged, a.graph)
     cpu = None if a.no_cpu_baseline else cpu_baseline(case.sb)
     del case
-    torch.cuda.empty_cache()
-    others, extras, seeds = {}, {}, []
+    settle()
+    others, extras, seeds, sweep = {}, {}, [], []
     for name in [x for x in a.also.split(",") if x and x != a.workload]:
         r, c2 = run_workload(name, a.steps, a.warmup, a.copies, a.verbose, a.num_splits, a.paged, a.graph)
         others[name] = r
         del c2
-        torch.cuda.empty_cache()
+        settle()
     if not a.no_extras:
         from paper_2604_16883_amd import synth
         # the headline workload over its repetition seeds: the realised skip ratio is quantised by the 8 groups, and
@@ -598,17 +635,28 @@ def main():
                 r["description"] += ", repetition seed %d: skip ratio %.3f, the paper's operating point" % (seed, rt["skip_ratio"])
                 extras["c3_skip0.625"] = r
             del c2
-            torch.cuda.empty_cache()
+            settle()
+        # latency against context length on the headline shape (the paper's latency study, Section 5.3: gains are small
+        # below 64K tokens and grow with the context), routed and dense on identical inputs
+        for L in CONTEXT_SWEEP:
+            r, c2 = run_workload("c3", a.steps, a.warmup, a.copies, a.verbose, seq_lens=[L], taus=False, prefill_anchors=False)
+            rt, dn = r["routed_tau0.55"], r["dense"]
+            sweep.append({"context": L, "skip_ratio": rt["skip_ratio"], "copies": r["copies"], "algorithmic_bytes": rt["algorithmic_bytes"],
+                          "us_per_step": rt["us_per_step"], "step_frac_of_peak": rt["step_frac_of_peak"],
+                          "dense_us_per_step": dn["us_per_step"], "dense_step_frac_of_peak": dn["step_frac_of_peak"],
+                          "routed_vs_dense_speedup": r["routed_vs_dense_speedup"]})
+            del c2
+            settle()
         # one long and several short sequences, contiguous and paged: where the balanced schedule has to pay
         r, c2 = run_workload("c1", a.steps, a.warmup, a.copies, a.verbose, seq_lens=RAGGED_LENS, taus=False)
         extras["c1_ragged"] = r
         del c2
-        torch.cuda.empty_cache()
+        settle()
         r, c2 = run_workload("c1", a.steps, a.warmup, a.copies, a.verbose, seq_lens=RAGGED_LENS, page_tokens=256, taus=False)
         r["description"] += ", paged (256-token pages, seeded random page order)"
         extras["c1_ragged_paged256"] = r
         del c2
-        torch.cuda.empty_cache()
+        settle()
 
     routed = main_res["routed_tau0.55"]
     # the paged entry point has no per-kernel events: the whole step stands in for the kernel there
@@ -644,6 +692,7 @@ def main():
         # the metric is quoted at 128K and 512K: every workload's headline figures, same protocol
         "also": {name: headline(r) for name, r in {a.workload: main_res, **others, **extras}.items()},
         "seeds": seeds,
+        "context_sweep": {"shape": "c3 (B1, 64/8 heads), tau 0.55", "points": sweep},
         "detail": {a.workload: main_res, **others, **extras},
     }
     if a.markdown:
