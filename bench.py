@@ -64,6 +64,15 @@ def measured_traffic(workload: str, mode: str):
     return r, "profiles/traffic.json: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by the copy kernel of the same run"
 
 
+def per_group_shares(units, P):
+    """The balanced schedule's choice, mirrored from the kernel: every Active Group gets workgroups of its own if at most
+    half as many groups are active as there are workgroups and the shares then occupy at least three quarters of them."""
+    U, A = sum(units), sum(1 for u in units if u)
+    if not U or 2 * A > P:
+        return False
+    return 4 * sum((u * (P - A) + U - 1) // U for u in units if u) >= 3 * P
+
+
 def partial_records(w, seq_lens, mask, plan):
     """Number of (head, workgroup) partial records the Split-K kernel writes for this mask."""
     B, Hq, Hkv = w.batch, w.n_q_heads, w.n_kv_heads
@@ -76,7 +85,7 @@ def partial_records(w, seq_lens, mask, plan):
     A = sum(1 for u in units if u)
     if U == 0:
         return 0
-    if 2 * A <= P:
+    if per_group_shares(units, P):
         # per-group shares: group i gets ceil(u_i (P - A) / U) workgroups of ceil(u_i / n_i) blocks each
         n = 0
         for u in units:
@@ -370,7 +379,7 @@ def timeline_report(name, tau, steps, copies, anchors_cached):
     busy = tp[..., 5] > 0                  # workgroups that streamed something
     units = [0 if m[b, g] else (int(sb.seq_lens[b]) + 63) // 64 for b in range(B) for g in range(Hkv)]
     U, A = sum(units), sum(1 for u in units if u)
-    if 2 * A <= grid and U:           # per-group shares: the largest share of any group
+    if per_group_shares(units, grid):           # the largest share of any group
         c = max((u + ((u * (grid - A) + U - 1) // U) - 1) // ((u * (grid - A) + U - 1) // U) for u in units if u)
     else:
         c = (U + grid - 1) // grid

@@ -102,7 +102,8 @@ typedef struct sr_plan {
  *                           out to one workgroup per compute unit (256), on the device, once
  *                           the skip decisions are known: every Active Group gets workgroups
  *                           in proportion to its blocks (or, with more than 128 Active
- *                           Groups, every workgroup an equal run of the blocks laid end to
+ *                           Groups, or where that would leave a quarter of the workgroups
+ *                           idle, every workgroup an equal run of the blocks laid end to
  *                           end), so the chunk length adapts to the skip pattern.
  *                           Needs B*H_kv <= 2048; larger batches fall back to fixed chunks.
  * The result does not depend on the schedule beyond fp32 rounding.

@@ -20,7 +20,8 @@
 //                  the 64-token blocks of the Active Groups only are dealt out: workgroups per
 //                  group in proportion to its blocks, one group per workgroup (or equal runs of
 //                  the blocks laid end to end when more than half as many groups are active as
-//                  there are workgroups).  Sink Groups cost nothing and the chip stays full
+//                  there are workgroups, or when shares per group would leave a quarter of the
+//                  workgroups idle).  Sink Groups cost nothing and the chip stays full
 //                  whatever the skip pattern is.
 //        fixed     the paper's literal Split-K: [0, L) cut into num_splits chunks, one
 //                  workgroup per (chunk, sequence, KV group); workgroups of Sink Groups

@@ -74,6 +74,10 @@ SR_HD uint32_t div_by(uint32_t x, uint32_t magic) {
 // workgroups (their sum is at most P), each taking ceil(u_i / n_i) consecutive blocks, so no workgroup works on two
 // groups.  share_records is the number of workgroups of a group that get any block: its partial records.
 SR_HD bool per_group_shares(int A, int P) { return A > 0 && 2 * A <= P; }
+// ... and only if the shares then occupy at least three quarters of the workgroups.  share_count leaves up to A of
+// them idle: 128 equally long Active Groups would get one workgroup each and half the chip would stand still, where
+// contiguous shares give every group two.  (Up to 64 Active Groups always pass: their shares occupy P - A >= 192.)
+SR_HD bool per_group_fills(int shares, int P) { return 4 * shares >= 3 * P; }
 SR_HD int share_count(int u, int U, int P, int A) {        // u (P - A) < 2^18 * 2^8: 32-bit arithmetic is exact
   return u > 0 ? (int)(((uint32_t)u * (uint32_t)(P - A) + (uint32_t)U - 1u) / (uint32_t)U) : 0;
 }

@@ -304,7 +304,8 @@ __global__ __launch_bounds__(kThreads, 2) void sr_partial_fixed_kernel(PartialAr
 //     (share_count), each a run of share_blocks consecutive blocks: every workgroup streams one group only.  A
 //     workgroup that changes groups drains and refills its load pipeline while the rest of the chip keeps the
 //     memory queues full, which costs it 3-4 us: with contiguous shares those workgroups ended the kernel.
-//   contiguous shares (more Active Groups than that): units are numbered group after group and workgroup p
+//   contiguous shares (more Active Groups than that, or per-group shares that would occupy less than three quarters of
+//     the workgroups: per_group_fills): units are numbered group after group and workgroup p
 //     owns units [p*c, (p+1)*c), c = ceil(U/P); partial record j of a group belongs to workgroup (start/c + j).
 // Workgroup 0 leaves the schedule in `sched` for the merge kernel: mode (1 = per-group), c, then per group
 // (blocks, workgroups) or (first unit, end unit).
@@ -439,34 +440,40 @@ __global__ __launch_bounds__(kThreads, 2) void sr_partial_balanced_kernel(Partia
   int U = 0, A = 0;
 #pragma unroll
   for (int u2 = 0; u2 < kWaves; ++u2) { U += wsum[u2]; A += wsum[kWaves + u2]; }
-  const bool per_group = per_group_shares(A, P);
+  bool per_group = per_group_shares(A, P);
   __syncthreads();                                // wsum is reused by the scan
-  // Pass 2: prefix sums of the workgroups per group (per-group shares) or of the blocks per group (contiguous).
+  // Pass 2: prefix sums of the workgroups per group (per-group shares) or of the blocks per group (contiguous).  Per-group
+  // shares that would leave more than a quarter of the workgroups idle are dropped for contiguous ones: one more scan.
   int carry = 0;
-  for (int base = 0; base < NG; base += kThreads) {
-    const int i = base + tid;
-    int v = 0;
-    if (i < NG) {
-      const int u = lens[i] > 0 ? (lens[i] + kBlock - 1) / kBlock : 0;
-      v = per_group ? share_count(u, U, P, A) : u;
+  for (int attempt = 0; attempt < 2; ++attempt) {
+    carry = 0;
+    for (int base = 0; base < NG; base += kThreads) {
+      const int i = base + tid;
+      int v = 0;
+      if (i < NG) {
+        const int u = lens[i] > 0 ? (lens[i] + kBlock - 1) / kBlock : 0;
+        v = per_group ? share_count(u, U, P, A) : u;
+      }
+      int x = v;                                   // inclusive scan inside the wavefront
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const int y = __shfl_up(x, o, 64);
+        if (lane >= o) x += y;
+      }
+      if (lane == 63) wsum[wave] = x;
+      __syncthreads();
+      int woff = 0;
+#pragma unroll
+      for (int u2 = 0; u2 < kWaves; ++u2) if (u2 < wave) woff += wsum[u2];
+      int tot = 0;
+#pragma unroll
+      for (int u2 = 0; u2 < kWaves; ++u2) tot += wsum[u2];
+      if (i < NG) start[i] = carry + woff + x - v;
+      carry += tot;
+      __syncthreads();
     }
-    int x = v;                                   // inclusive scan inside the wavefront
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-      const int y = __shfl_up(x, o, 64);
-      if (lane >= o) x += y;
-    }
-    if (lane == 63) wsum[wave] = x;
-    __syncthreads();
-    int woff = 0;
-#pragma unroll
-    for (int u2 = 0; u2 < kWaves; ++u2) if (u2 < wave) woff += wsum[u2];
-    int tot = 0;
-#pragma unroll
-    for (int u2 = 0; u2 < kWaves; ++u2) tot += wsum[u2];
-    if (i < NG) start[i] = carry + woff + x - v;
-    carry += tot;
-    __syncthreads();
+    if (!per_group || per_group_fills(carry, P)) break;      // carry is the same in every thread
+    per_group = false;
   }
   if (tid == 0) { start[NG] = carry; first_group = -1; }
   const int c = per_group ? 0 : (U + P - 1) / P;

@@ -164,8 +164,10 @@ static void check_pages() {
         CHECK(r <= kBalancedGrid + 1 && r <= u[i]);                    // fits the reserved record slots
         total += n;
       }
-      CHECK(total <= P);
+      CHECK(total <= P && total >= P - A);
+      CHECK(A > 64 || per_group_fills((int)total, P));             // the register-built schedule never needs the check
     }
+    CHECK(per_group_fills(192, P) && !per_group_fills(191, P));    // 128 equal groups: one workgroup each, dropped
     CHECK(!per_group_shares(0, P) && !per_group_shares(P / 2 + 1, P) && per_group_shares(P / 2, P));
     CHECK(share_count(0, 100, P, 3) == 0 && share_records(0, 0) == 0);
     CHECK(share_count(1 << 18, 1 << 18, P, 1) == P - 1);               // one group alone takes P - 1 workgroups

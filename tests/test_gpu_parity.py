@@ -142,6 +142,23 @@ def test_heads_with_more_records_than_one_merge_sweep(shape):
     assert res["plan"].slots_per_head >= records
 
 
+def test_equal_groups_whose_own_shares_would_leave_half_the_chip_idle():
+    """128 equally long (sequence, group) pairs, routing off: per-group shares would be one workgroup each (128 of 256
+    busy), so the schedule falls back to contiguous shares (two workgroups per group); 100 such pairs keep their own
+    shares (two each).  Both are built in LDS (more than 64 groups)."""
+    import bench
+    for B in (64, 50):
+        Hq, Hkv, L = 4, 2, 700
+        w = synth.Workload("cliff", B, Hq, Hkv, L, 0.5, base_seed=520 + B, planted_per_head=4)
+        sb = synth.generate(w)
+        assert bench.per_group_shares([(L + 63) // 64] * (B * Hkv), 256) == (B == 50)
+        res = gu.run_hip(sb.q, sb.k, sb.v, sb.seq_lens, routing_enabled=False)
+        ref = oracle.decode(sb.q, sb.k, sb.v, sb.seq_lens, want_dense=True, routing_enabled=False)
+        rep = gu.compare(res, ref, w.group_size, "cliff B=%d" % B)
+        print("cliff", B, rep, flush=True)
+        assert res["plan"].schedule == 1
+
+
 def test_edge_lengths():
     # lengths 0 and 1, exactly one block, one block + 1, all with a poisoned tail beyond seq_len
     w = synth.Workload("edge", 6, 8, 2, 300, 0.5, base_seed=77)
