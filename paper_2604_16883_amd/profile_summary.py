@@ -9,6 +9,7 @@ for `roofline.traffic`).
     fetch/f_counter_collection.csv                        rocprofv3 --pmc FETCH_SIZE
     write/w_counter_collection.csv                        rocprofv3 --pmc WRITE_SIZE
     trace.log                                             stdout of the traced run (bench.py's JSON line)
+    util/, insts/, tcc/ + util.log, insts.log, tcc.log    optional: three more --pmc runs (UTIL_PASSES) and their stdout
 The partial kernel's dispatches are attributed to the benchmark's modes by order: the JSON line carries how
 many launches each mode makes.  Counter units are scaled by the plain copy kernel of known size that every
 bench run dispatches once.
@@ -68,6 +69,65 @@ def counters(path: str):
         if s:
             d[s].append(float(r["Counter_Value"]))
     return d
+
+
+def counter_table(path: str):
+    """{(kernel, counter): [value per dispatch, in dispatch order]} of a counter_collection.csv that holds several
+    counters; rows of one dispatch and counter (one per hardware instance) are summed."""
+    acc = collections.OrderedDict()
+    for r in csv.DictReader(open(path)):
+        s = short(r["Kernel_Name"])
+        if s:
+            key = (s, r["Counter_Name"], int(r["Dispatch_Id"]))
+            acc[key] = acc.get(key, 0.0) + float(r["Counter_Value"])
+    out = collections.defaultdict(list)
+    for (s, name, did) in sorted(acc, key=lambda k: k[2]):
+        out[(s, name)].append(acc[(s, name, did)])
+    return out
+
+
+UTIL_PASSES = (("util", "MfmaUtil VALUBusy LDSBankConflict OccupancyPercent"),
+               ("insts", "SQ_INSTS_VALU SQ_INSTS_MFMA SQ_INSTS_VMEM_RD SQ_INSTS_LDS SQ_WAVES SQ_INSTS_SALU"),
+               ("tcc", "TCC_HIT TCC_MISS TCC_REQ"))
+
+
+def utilisation_section(base, wl, cmd_short, det):
+    """Optional: utilisation, instruction and L2 counters of the partial kernel from three further runs (directories
+    util/, insts/, tcc/ under <dir>, each with its own trace-free --pmc pass and its own bench line in <pass>.log)."""
+    have = [(d, names) for d, names in UTIL_PASSES if glob.glob(os.path.join(base, d, "**", "*counter_collection.csv"), recursive=True)]
+    if not have:
+        return []
+    out = ["", "## utilisation, instruction and L2 counters of the partial kernel (further runs, counters only)", ""]
+    for d, names in have:
+        out.append("    rocprofv3 --pmc %s --output-format csv -d $D/%s -o p -- %s > $D/%s.log" % (names, d, cmd_short, d))
+    rows, labels = [], None
+    for d, names in have:
+        line = bench_line(os.path.join(base, d + ".log"))
+        plan, warm = line["detail"][wl]["dispatch_plan"], line["warmup"]
+        labels = [label for label, _ in plan]
+        tab = counter_table(find(os.path.join(base, d), "*counter_collection.csv"))
+        for name in names.split():
+            vals = tab.get(("sr_partial", name))
+            if not vals:
+                continue
+            per = split_by_plan(vals, plan)
+            rows.append((name, [sum(per[l][warm:]) / max(len(per[l][warm:]), 1) for l in labels]))
+    blocks = {l: max(det[l]["algorithmic_bytes"] // 32768, 1) for l in labels}      # 64-token blocks streamed, about
+    out += ["", "Means per dispatch of the partial kernel (warm-up dispatches left out); blocks of 64 tokens streamed: " +
+            ", ".join("%s %d" % (l, blocks[l]) for l in labels) + ".", "",
+            "| counter | " + " | ".join(labels) + " |", "|---|" + "---|" * len(labels)]
+    for name, vals in rows:
+        out.append("| %s | %s |" % (name, " | ".join("%.4g" % v for v in vals)))
+    by = dict(rows)
+    if "SQ_INSTS_MFMA" in by and "SQ_INSTS_VALU" in by and "SQ_INSTS_VMEM_RD" in by:
+        i = len(labels) - 1          # the dense mode streams the most blocks
+        out += ["", "Per 64-token block (%s): %.0f MFMA, %.0f VALU and %.1f vector-memory read instructions per wavefront-block." % (
+            labels[i], by["SQ_INSTS_MFMA"][i] / blocks[labels[i]], by["SQ_INSTS_VALU"][i] / blocks[labels[i]],
+            by["SQ_INSTS_VMEM_RD"][i] / blocks[labels[i]])]
+    if "TCC_REQ" in by and "TCC_HIT" in by:
+        out += ["L2: %s requests of 128 bytes per dispatch, %s of them hits: a pure stream, nothing is re-read." % (
+            " / ".join("%.3g" % v for v in by["TCC_REQ"]), " / ".join("%.1f %%" % (100 * h / max(r, 1)) for h, r in zip(by["TCC_HIT"], by["TCC_REQ"])))]
+    return out
 
 
 def main(argv):
@@ -141,6 +201,7 @@ def main(argv):
     out += ["", "Merge kernel traffic (fetched / written MB per dispatch): " +
             "; ".join("%s %.2f / %.2f" % (label, record[label]["merge_fetch_bytes"] / 1e6, record[label]["merge_write_bytes"] / 1e6)
                       for label, _ in plan) + ".", ""]
+    out += utilisation_section(base, wl, "python3 $R/bench.py --workload %s --lean --steps 5 --warmup 2" % wl, det)
     os.makedirs(os.path.join(ROOT, "profiles"), exist_ok=True)
     md = os.path.join(ROOT, "profiles", "sr_partial_balanced_kernel_%s.md" % wl)
     with open(md, "w") as fh:

@@ -133,6 +133,17 @@ def test_profile_summary_end_to_end_on_synthetic_rocprof_output(tmp_path, monkey
             for i, _ in enumerate(durs):
                 bytes_ = (2048000 if i < 3 else 4096000) if d == "fetch" else 10240
                 f.write('"%s",%d\n"%s",%d\n' % (part, bytes_ // unit, comb, 1))
+    # an optional further pass with two instruction counters, two hardware instances per dispatch (summed)
+    (base / "insts").mkdir()
+    (base / "insts.log").write_text(json.dumps(line) + "\n")
+    with open(base / "insts" / "p_counter_collection.csv", "w") as f:
+        f.write("Dispatch_Id,Kernel_Name,Counter_Name,Counter_Value\n")
+        for i, _ in enumerate(durs):
+            blocks = 62 if i < 3 else 125
+            for name, per_block in (("SQ_INSTS_MFMA", 48), ("SQ_INSTS_VALU", 400), ("SQ_INSTS_VMEM_RD", 32)):
+                for inst in range(2):
+                    f.write('%d,"%s",%s,%d\n' % (2 * i + 1, part, name, blocks * per_block // 2))
+            f.write('%d,"%s",SQ_INSTS_MFMA,%d\n' % (2 * i + 2, comb, 0))
     monkeypatch.setattr(profile_summary, "ROOT", str(tmp_path))
     profile_summary.main(["x", str(base), "cX"])
     rec = json.load(open(tmp_path / "profiles" / "traffic.json"))["cX"]
@@ -142,4 +153,5 @@ def test_profile_summary_end_to_end_on_synthetic_rocprof_output(tmp_path, monkey
     assert r["kernel_source_sha"] == bench.kernel_source_sha() and r["fetch_unit_bytes"] == 2048.0
     md = open(tmp_path / "profiles" / "sr_partial_balanced_kernel_cX.md").read()
     assert "| routed_tau0.55 | 0.500 | 2.1 / 2.0 | 2.05 | 2.05 | 0.01 | 1.0050 |" in md and "rocprofv3 --pmc FETCH_SIZE" in md
+    assert "| SQ_INSTS_MFMA | 2976 | 6000 |" in md and "(dense): 48 MFMA, 400 VALU and 32.0 vector-memory" in md
     assert "| 3.0 | 1.50 |" in md                                 # merge kernel duration and the gap behind the partial kernel
