@@ -47,8 +47,18 @@ struct PartialArgs {
 // K tile T, step j: lane (r16, kg) holds row row0+16T+r16, elements (4j+kg)*8 .. +8.
 // A row reaches the wavefront as 64-byte pieces, two loads per 128-byte line, so these stay
 // ordinary cached loads (the second piece of a line hits); a non-temporal hint here costs bandwidth.
+// kExact: the whole block lies inside the sequence, so no row is clamped; the address is then a wavefront-uniform
+// base plus a lane offset that never changes (lane_k / lane_v below), which needs no vector address arithmetic.
+template <bool kExact>
 __device__ __forceinline__ void load_k_tile(uint4 (&kr)[4], const uint4* __restrict__ Kbase, int row0, int T,
                                             int r16, int kg, int row_last) {
+  if (kExact) {
+    const uint4* p = Kbase + (size_t)(row0 + 16 * T) * 16;          // uniform
+    const unsigned lane_k = (unsigned)(r16 * 16 + kg);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) kr[j] = p[lane_k + 4u * j];
+    return;
+  }
   int row = row0 + 16 * T + r16;
   row = row < row_last ? row : row_last;
   const uint4* p = Kbase + (size_t)row * 16 + kg;
@@ -58,8 +68,16 @@ __device__ __forceinline__ void load_k_tile(uint4 (&kr)[4], const uint4* __restr
 
 // V tile T, row r: lane (r16, kg) holds row row0+16T+4kg+r, elements 8*r16 .. +8: each load
 // instruction covers four whole 256-byte rows.
+template <bool kExact>
 __device__ __forceinline__ void load_v_tile(uint4 (&vr)[4], const uint4* __restrict__ Vbase, int row0, int T,
                                             int r16, int kg, int row_last) {
+  if (kExact) {
+    const uint4* p = Vbase + (size_t)(row0 + 16 * T) * 16;          // uniform
+    const unsigned lane_v = (unsigned)(kg * 64 + r16);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) vr[r] = load_stream(p + (lane_v + 16u * r));
+    return;
+  }
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
     int row = row0 + 16 * T + 4 * kg + r;
@@ -79,7 +97,9 @@ struct WaveState {
 // so the loop body has no conditional loads and the wait counts the compiler inserts stay exact.
 // The scheduling barriers keep the compiler from hoisting a prefetch above the MFMAs that still
 // read its registers (it would need a second register set) or sinking it to the end of the block.
-template <bool kPrefetch>
+// kExact: the current block lies inside [0, t_end) (no score is masked) and the prefetched one inside the sequence (no row
+// is clamped): every block but the last one or two of a range.
+template <bool kPrefetch, bool kExact>
 __device__ __forceinline__ void block_step(WaveState& w, uint4 (&kr)[4][4], uint4 (&vr)[4][4], const bf16x8 (&qb)[4],
                                            const uint4* __restrict__ Kn, const uint4* __restrict__ Vn, int row0_n, int row_last_n,
                                            int tok0, int t_end, int r16, int kg, float scale_log2) {
@@ -92,7 +112,7 @@ __device__ __forceinline__ void block_step(WaveState& w, uint4 (&kr)[4][4], uint
     for (int j = 0; j < 4; ++j)
       sc[T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kr[T][j]), qb[j], sc[T], 0, 0, 0);
     __builtin_amdgcn_sched_barrier(0);
-    if (kPrefetch) load_k_tile(kr[T], Kn, row0_n, T, r16, kg, row_last_n);
+    if (kPrefetch) load_k_tile<kExact>(kr[T], Kn, row0_n, T, r16, kg, row_last_n);
     __builtin_amdgcn_sched_barrier(0);
   }
   // ---- online softmax over the block
@@ -101,9 +121,11 @@ __device__ __forceinline__ void block_step(WaveState& w, uint4 (&kr)[4][4], uint
   for (int T = 0; T < 4; ++T)
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      const int tok = tok0 + 16 * T + 4 * kg + r;
       float z = sc[T][r] * scale_log2;
-      z = tok < t_end ? z : -INFINITY;
+      if (!kExact) {
+        const int tok = tok0 + 16 * T + 4 * kg + r;
+        z = tok < t_end ? z : -INFINITY;
+      }
       sc[T][r] = z;
       bm = fmaxf(bm, z);
     }
@@ -167,7 +189,7 @@ __device__ __forceinline__ void block_step(WaveState& w, uint4 (&kr)[4][4], uint
       }
     }
     __builtin_amdgcn_sched_barrier(0);
-    if (kPrefetch) { load_v_tile(vr[T], Vn, row0_n, T, r16, kg, row_last_n); load_v_tile(vr[T + 1], Vn, row0_n, T + 1, r16, kg, row_last_n); }
+    if (kPrefetch) { load_v_tile<kExact>(vr[T], Vn, row0_n, T, r16, kg, row_last_n); load_v_tile<kExact>(vr[T + 1], Vn, row0_n, T + 1, r16, kg, row_last_n); }
     __builtin_amdgcn_sched_barrier(0);
   }
 }
@@ -223,9 +245,9 @@ __device__ __forceinline__ void attend_range(const PartialArgs& a, int b, int g,
       const size_t base = slab_base(kPaged ? page_of(a.pm, b, tok0) : 0);
       const int row0 = slab_row(tok0), row_last = row0 + (last - tok0);
 #pragma unroll
-      for (int T = 0; T < 4; ++T) load_k_tile(kr[T], K4 + base, row0, T, r16, kg, row_last);
+      for (int T = 0; T < 4; ++T) load_k_tile<false>(kr[T], K4 + base, row0, T, r16, kg, row_last);
 #pragma unroll
-      for (int T = 0; T < 4; ++T) load_v_tile(vr[T], V4 + base, row0, T, r16, kg, row_last);
+      for (int T = 0; T < 4; ++T) load_v_tile<false>(vr[T], V4 + base, row0, T, r16, kg, row_last);
     }
     int next = tok0 + kStep;
     // paged: the page of a block is looked up one iteration before the block is prefetched
@@ -233,18 +255,29 @@ __device__ __forceinline__ void attend_range(const PartialArgs& a, int b, int g,
 #if SR_TIMELINE
     bool first_step = a.timeline && a.timeline[(size_t)blockIdx.x * kTimelinePartialStamps + 4] == 0;
 #endif
-    while (next < t_end) {
+    // every block but the last of a range lies inside [0, t_end), and the prefetched one inside the sequence unless it is
+    // the sequence's ragged last block: those steps mask no score and clamp no row
+    while (next + kBlock <= t_end) {
       const size_t base = slab_base(page_n);
-      const int row0 = slab_row(next), row_last = row0 + (last - next);
+      const int row0 = slab_row(next);
       if (kPaged) page_n = page_of(a.pm, b, min(next + kStep, last));
-      block_step<true>(w, kr, vr, qb, K4 + base, V4 + base, row0, row_last, tok0, t_end, r16, kg, a.scale_log2);
+      block_step<true, true>(w, kr, vr, qb, K4 + base, V4 + base, row0, 0, tok0, t_end, r16, kg, a.scale_log2);
 #if SR_TIMELINE
       if (first_step) { SR_STAMP(a.timeline, kTimelinePartialStamps, 4); first_step = false; }
 #endif
       tok0 = next;
       next += kStep;
     }
-    block_step<false>(w, kr, vr, qb, K4, V4, 0, 0, tok0, t_end, r16, kg, a.scale_log2);
+    if (next < t_end) {                     // the range ends with a ragged block, and it is this wavefront's
+      const size_t base = slab_base(page_n);
+      const int row0 = slab_row(next), row_last = row0 + (last - next);
+      block_step<true, false>(w, kr, vr, qb, K4 + base, V4 + base, row0, row_last, tok0, t_end, r16, kg, a.scale_log2);
+#if SR_TIMELINE
+      if (first_step) { SR_STAMP(a.timeline, kTimelinePartialStamps, 4); first_step = false; }
+#endif
+      tok0 = next;
+    }
+    block_step<false, false>(w, kr, vr, qb, K4, V4, 0, 0, tok0, t_end, r16, kg, a.scale_log2);
 #if SR_TIMELINE
     if (first_step) SR_STAMP(a.timeline, kTimelinePartialStamps, 4);
 #endif
