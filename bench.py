@@ -37,6 +37,7 @@ TRAFFIC_JSON = os.path.join(ROOT, "profiles", "traffic.json")
 # sources that decide what the partial kernel reads and writes: a counter record is valid for these only
 KERNEL_SOURCES = ["sr_config.h", "sr_common.h", "sr_route.h", "sr_partial.h"]
 RAGGED_LENS = [32768, 20011, 4097, 65]      # c1-shaped batch with one long and several short sequences
+PRECONDITION_S = 0.1      # seconds of untimed calls in front of every timed mode (see precondition)
 CONTEXT_SWEEP = [8192, 16384, 32768, 65536, 131072, 262144]   # c3-shaped layer at shorter contexts (512K is the headline)
 
 
@@ -130,6 +131,19 @@ def time_steps(fn, steps, warmup):
         fn()
     torch.cuda.synchronize()
     return (time.perf_counter() - t0) / steps * 1e6
+
+
+def precondition(fn, seconds=0.1):
+    """Keeps the device busy with the calls about to be timed for `seconds` before their warm-up steps.  After idling
+    (the wait in settle(), a process start) the first 8-10 ms of work run up to 6 % slower and the step time keeps
+    falling slightly for some 100 ms (512K-context step: 89.2 us in the first 9 ms, 86.8-87.2 us until 80 ms, then
+    86.5 us), which 50 warm-up steps of 10-90 us do not cover; a serving device is never idle between decode steps."""
+    import torch
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < seconds:
+        for _ in range(50):
+            fn()
+        torch.cuda.synchronize()
 
 
 def settle():
@@ -235,8 +249,16 @@ class Case:
             self.call(p, it[0])
             it[0] += 1
 
+        launches = [0]
+
+        def counted():
+            step()
+            launches[0] += 1
+
+        precondition(counted, PRECONDITION_S)
+        leading = launches[0] + warmup              # launches of this mode before the first timed one
         us = time_steps(step, steps, warmup)
-        launches = warmup + steps
+        launches = leading + steps
         graph_us = None
         if use_graph:
             # the same steps replayed from one HIP graph (one decode call per K/V copy)
@@ -292,7 +314,7 @@ class Case:
             "anchors": "prefill-cached k0 and k0_norm" if (cached_anchors and routing) else ("row 0 of the cache" if routing else "unused"),
             "schedule": "balanced" if plan.schedule else "fixed", "page_tokens": self.page_tokens,
             "partial_grid": int(plan.partial_grid), "partial_records": partial_records(self.w, self.sb.seq_lens, m, plan),
-            "partial_kernel_launches": launches,
+            "partial_kernel_launches": launches, "leading_untimed_launches": leading,
         }
 
 
@@ -316,7 +338,7 @@ def run_workload(name, steps, warmup, copies, verbose, num_splits=0, page_tokens
     for label, m in modes:
         r = case.time_mode(steps, warmup, **m, **kw)
         res[label] = r
-        plan_order.append([label, r["partial_kernel_launches"]])
+        plan_order.append([label, r["partial_kernel_launches"], r["leading_untimed_launches"]])
         if verbose:
             print(name, label, r, file=sys.stderr, flush=True)
     res["dispatch_plan"] = plan_order

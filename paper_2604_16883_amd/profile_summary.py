@@ -6,8 +6,8 @@ for `roofline.traffic`).
 
 <dir> holds, as written by the commands the summary itself lists:
     trace/t_kernel_trace.csv, trace/t_kernel_stats.csv    rocprofv3 --kernel-trace --stats
-    fetch/f_counter_collection.csv                        rocprofv3 --pmc FETCH_SIZE
-    write/w_counter_collection.csv                        rocprofv3 --pmc WRITE_SIZE
+    fetch/f_counter_collection.csv, fetch.log             rocprofv3 --pmc FETCH_SIZE and the run's stdout
+    write/w_counter_collection.csv, write.log             rocprofv3 --pmc WRITE_SIZE and the run's stdout
     trace.log                                             stdout of the traced run (bench.py's JSON line)
     util/, insts/, tcc/ + util.log, insts.log, tcc.log    optional: three more --pmc runs (UTIL_PASSES) and their stdout
 The partial kernel's dispatches are attributed to the benchmark's modes by order: the JSON line carries how
@@ -53,8 +53,10 @@ def bench_line(path: str) -> dict:
 
 
 def split_by_plan(values, plan):
+    """plan: [label, launches of the mode, (optional) how many of them come before the first timed one]."""
     out, i = {}, 0
-    for label, n in plan:
+    for entry in plan:
+        label, n = entry[0], entry[1]
         out[label] = values[i:i + n]
         i += n
     if i != len(values):
@@ -69,6 +71,11 @@ def counters(path: str):
         if s:
             d[s].append(float(r["Counter_Value"]))
     return d
+
+
+def leading(plan, warmup):
+    """Per mode, the dispatches in front of the first timed one (device preconditioning + warm-up steps): left out of means."""
+    return {e[0]: (e[2] if len(e) > 2 else warmup) for e in plan}
 
 
 def counter_table(path: str):
@@ -103,15 +110,16 @@ def utilisation_section(base, wl, cmd_short, det):
     rows, labels = [], None
     for d, names in have:
         line = bench_line(os.path.join(base, d + ".log"))
-        plan, warm = line["detail"][wl]["dispatch_plan"], line["warmup"]
-        labels = [label for label, _ in plan]
+        plan = line["detail"][wl]["dispatch_plan"]
+        lead = leading(plan, line["warmup"])
+        labels = [e[0] for e in plan]
         tab = counter_table(find(os.path.join(base, d), "*counter_collection.csv"))
         for name in names.split():
             vals = tab.get(("sr_partial", name))
             if not vals:
                 continue
             per = split_by_plan(vals, plan)
-            rows.append((name, [sum(per[l][warm:]) / max(len(per[l][warm:]), 1) for l in labels]))
+            rows.append((name, [sum(per[l][lead[l]:]) / max(len(per[l][lead[l]:]), 1) for l in labels]))
     blocks = {l: max(det[l]["algorithmic_bytes"] // 32768, 1) for l in labels}      # 64-token blocks streamed, about
     out += ["", "Means per dispatch of the partial kernel (warm-up dispatches left out); blocks of 64 tokens streamed: " +
             ", ".join("%s %d" % (l, blocks[l]) for l in labels) + ".", "",
@@ -143,10 +151,11 @@ def main(argv):
     out = ["# rocprofv3 summary: sr_partial_balanced_kernel and sr_combine_kernel, workload %s (%s, bf16)" % (wl, det["description"]), "",
            "Commands (run from /tmp with TMPDIR=/tmp on the MI355X box, R = repository root, D = $R/gpurun_out/prof_%s):" % wl, "",
            "    rocprofv3 --kernel-trace --stats --output-format csv -d $D/trace -o t -- %s > $D/trace.log" % cmd,
-           "    rocprofv3 --pmc FETCH_SIZE --output-format csv -d $D/fetch -o f -- %s" % cmd,
-           "    rocprofv3 --pmc WRITE_SIZE --output-format csv -d $D/write -o w -- %s" % cmd,
+           "    rocprofv3 --pmc FETCH_SIZE --output-format csv -d $D/fetch -o f -- %s > $D/fetch.log" % cmd,
+           "    rocprofv3 --pmc WRITE_SIZE --output-format csv -d $D/write -o w -- %s > $D/write.log" % cmd,
            "    python3 -m paper_2604_16883_amd.profile_summary $D %s" % wl, "",
-           "Each run launches the modes below in this order; per mode %d warm-up + %d timed + %d (step-time spread) + %d (per-kernel HIP "
+           "Each run launches the modes below in this order; per mode 0.1 s of untimed calls (the device is idle at process start and "
+           "runs slower for its first milliseconds of work), then %d warm-up + %d timed + %d (step-time spread) + %d (per-kernel HIP "
            "events) launches at most (the last two are capped at 200 and 100).  The routing probe is fused into the partial kernel, so no sr_probe_kernel is dispatched.  sr_read_probe / "
            "sr_copy_probe are the benchmark's calibration kernels (2 GiB streaming read; 1 GiB copy of known traffic)."
            % (warmup, steps, steps, steps), "",
@@ -168,9 +177,20 @@ def main(argv):
     by_p, by_c, by_g = split_by_plan(dur_p, plan), split_by_plan(dur_c, plan), split_by_plan(gaps, plan)
     f, w = counters(find(base, "f_counter_collection.csv")), counters(find(base, "w_counter_collection.csv"))
     fscale, wscale = COPY_BYTES / f["sr_copy_probe"][0], COPY_BYTES / w["sr_copy_probe"][0]
-    f_p, w_p = split_by_plan(f["sr_partial"], plan), split_by_plan(w["sr_partial"], plan)
-    f_c, w_c = split_by_plan(f["sr_combine"], plan), split_by_plan(w["sr_combine"], plan)
-    out += ["", "## per mode: partial kernel (mean over the mode's dispatches, the first %d warm-up ones left out)" % warmup, "",
+
+    def plan_of(run):
+        """The dispatch plan of a counter run: its own bench line if its stdout was kept (the number of preconditioning
+        launches depends on how fast the run is), else that of the traced run."""
+        path = os.path.join(base, run + ".log")
+        return bench_line(path)["detail"][wl]["dispatch_plan"] if os.path.exists(path) else plan
+
+    plan_f, plan_w = plan_of("fetch"), plan_of("write")
+    lead_f, lead_w = leading(plan_f, warmup), leading(plan_w, warmup)
+    f_p, w_p = split_by_plan(f["sr_partial"], plan_f), split_by_plan(w["sr_partial"], plan_w)
+    f_c, w_c = split_by_plan(f["sr_combine"], plan_f), split_by_plan(w["sr_combine"], plan_w)
+    lead = leading(plan, warmup)
+    out += ["", "## per mode: partial kernel (mean over the mode's dispatches, those in front of the first timed step left out: "
+            "device preconditioning and %d warm-up steps)" % warmup, "",
             "Durations from the kernel trace (dispatch begin to end, the interval bench.py's HIP events attached to the launch "
             "measure when no profiler runs; under the profiler those events read about 10 us more and are not shown).  The gap is "
             "between the trace's end of the partial kernel and begin of the merge kernel.  Bytes: FETCH_SIZE / "
@@ -183,24 +203,26 @@ def main(argv):
         return sum(v) / max(len(v), 1)
 
     record = {}
-    for label, _ in plan:
+    for label in [e[0] for e in plan]:
         m = det[label]
-        d = by_p[label][warmup:]
-        fb, wb = mean(f_p[label][warmup:]) * fscale, mean(w_p[label][warmup:]) * wscale
+        k = lead[label]
+        d = by_p[label][k:]
+        kf, kw = lead_f[label], lead_w[label]
+        fb, wb = mean(f_p[label][kf:]) * fscale, mean(w_p[label][kw:]) * wscale
         ab = m["algorithmic_bytes"]
         out.append("| %s | %.3f | %.1f / %.1f | %.2f | %.2f | %.2f | %.4f | %.0f | %.1f %% | %.1f | %.2f |" % (
             label, m["skip_ratio"], mean(d), min(d), ab / 1e6, fb / 1e6, wb / 1e6, (fb + wb) / ab,
-            ab / mean(d) / 1e3, ab / mean(d) / 1e3 / 80.0, mean(by_c[label][warmup:]), mean(by_g[label][warmup:])))
+            ab / mean(d) / 1e3, ab / mean(d) / 1e3 / 80.0, mean(by_c[label][k:]), mean(by_g[label][k:])))
         record[label] = {"kernel": "sr_partial_balanced_kernel", "fetch_bytes": round(fb), "write_bytes": round(wb),
                          "algorithmic_bytes": ab, "trace_us_mean": round(mean(d), 2), "trace_us_min": round(min(d), 2),
-                         "merge_fetch_bytes": round(mean(f_c[label][warmup:]) * fscale),
-                         "merge_write_bytes": round(mean(w_c[label][warmup:]) * wscale),
-                         "merge_trace_us_mean": round(mean(by_c[label][warmup:]), 2),
+                         "merge_fetch_bytes": round(mean(f_c[label][kf:]) * fscale),
+                         "merge_write_bytes": round(mean(w_c[label][kw:]) * wscale),
+                         "merge_trace_us_mean": round(mean(by_c[label][k:]), 2),
                          "fetch_unit_bytes": round(fscale, 2), "write_unit_bytes": round(wscale, 2),
                          "kernel_source_sha": kernel_source_sha(), "command": cmd}
     out += ["", "Merge kernel traffic (fetched / written MB per dispatch): " +
             "; ".join("%s %.2f / %.2f" % (label, record[label]["merge_fetch_bytes"] / 1e6, record[label]["merge_write_bytes"] / 1e6)
-                      for label, _ in plan) + ".", ""]
+                      for label in [e[0] for e in plan]) + ".", ""]
     out += utilisation_section(base, wl, "python3 $R/bench.py --workload %s --lean --steps 5 --warmup 2" % wl, det)
     os.makedirs(os.path.join(ROOT, "profiles"), exist_ok=True)
     md = os.path.join(ROOT, "profiles", "sr_partial_balanced_kernel_%s.md" % wl)

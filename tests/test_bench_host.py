@@ -84,6 +84,9 @@ def test_dispatches_are_split_by_the_plan():
     assert profile_summary.split_by_plan([1, 2, 3, 4, 5], plan) == {"a": [1, 2, 3], "b": [4, 5]}
     with pytest.raises(SystemExit):
         profile_summary.split_by_plan([1, 2, 3, 4], plan)
+    # a third entry says how many of a mode's launches come before its first timed step; without it, the warm-up count
+    assert profile_summary.split_by_plan([1, 2, 3, 4, 5], [["a", 3, 2], ["b", 2, 1]]) == {"a": [1, 2, 3], "b": [4, 5]}
+    assert profile_summary.leading([["a", 3, 2], ["b", 2]], 1) == {"a": 2, "b": 1}
     assert profile_summary.short("void (anonymous namespace)::sr_partial_balanced_kernel<true, false>(PartialArgs)") == "sr_partial"
     assert profile_summary.short("at::native::vectorized_elementwise_kernel") is None
 
