@@ -122,22 +122,26 @@ def algorithmic_bytes(w, seq_lens, mask, plan):
 
 
 def time_steps(fn, steps, warmup, both=False):
-    """`warmup` untimed calls, then exactly `steps` calls between two device synchronisations.  The figure is the time
-    the device took for them: two events on the launch stream, the first recorded behind the first synchronisation, the
-    second behind the last call.  The host clock around the same bracket also counts the host's wake-up after the last
-    kernel (15-25 us per bracket here: 1 us per step at 20 steps, 0.04 at 500); with `both` it is returned as well."""
+    """`warmup` untimed calls, then exactly `steps` timed calls between two device synchronisations.  The figure is the
+    time the device took for them: two events on the launch stream.  One more untimed call follows the first
+    synchronisation and the first event is recorded behind it, so that the event's time stamp is taken when that call
+    ends, with the first timed call already queued: otherwise the device idles until the host's first launch arrives and
+    a short run is charged for it (about 0.5 us per step at 20 steps).  The host clock around the same bracket (over all
+    `steps` + 1 calls) also counts the host's wake-up after the last kernel, 15-25 us per bracket: 1 us per step at 20
+    steps, 0.04 at 500; with `both` it is returned as well."""
     import torch
     for _ in range(warmup):
         fn()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    fn()
     e0.record()
     for _ in range(steps):
         fn()
     e1.record()
     torch.cuda.synchronize()
-    host = (time.perf_counter() - t0) / steps * 1e6
+    host = (time.perf_counter() - t0) / (steps + 1) * 1e6
     dev = e0.elapsed_time(e1) * 1e3 / steps
     return (dev, host) if both else dev
 
@@ -265,7 +269,7 @@ class Case:
             launches[0] += 1
 
         precondition(counted, PRECONDITION_S)
-        leading = launches[0] + warmup              # launches of this mode before the first timed one
+        leading = launches[0] + warmup + 1          # launches of this mode before the first timed one
         us, host_us = time_steps(step, steps, warmup, both=True)
         launches = leading + steps
         graph_us = None
@@ -283,7 +287,7 @@ class Case:
                     step()
             reps = max(1, steps // self.copies)
             graph_us = time_steps(g.replay, reps, max(1, warmup // self.copies)) / self.copies
-            launches += 1 + self.copies * (reps + max(1, warmup // self.copies))
+            launches += 1 + self.copies * (reps + 1 + max(1, warmup // self.copies))
         # spread of the step time: one event between consecutive asynchronous steps, same rotation
         n_marks, n_prof = min(steps, 200), min(steps, 100)
         marks = [torch.cuda.Event(enable_timing=True) for _ in range(n_marks + 1)]
