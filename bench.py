@@ -289,7 +289,7 @@ class Case:
             graph_us = time_steps(g.replay, reps, max(1, warmup // self.copies)) / self.copies
             launches += 1 + self.copies * (reps + 1 + max(1, warmup // self.copies))
         # spread of the step time: one event between consecutive asynchronous steps, same rotation
-        n_marks, n_prof = min(steps, 200), min(steps, 100)
+        n_marks, n_prof = min(max(steps, 50), 200), 100      # not fewer when a run times only a few steps
         marks = [torch.cuda.Event(enable_timing=True) for _ in range(n_marks + 1)]
         it[0] = 0
         for s in range(n_marks):

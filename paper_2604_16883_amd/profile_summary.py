@@ -155,10 +155,10 @@ def main(argv):
            "    rocprofv3 --pmc WRITE_SIZE --output-format csv -d $D/write -o w -- %s > $D/write.log" % cmd,
            "    python3 -m paper_2604_16883_amd.profile_summary $D %s" % wl, "",
            "Each run launches the modes below in this order; per mode 0.1 s of untimed calls (the device is idle at process start and "
-           "runs slower for its first milliseconds of work), then %d warm-up + %d timed + %d (step-time spread) + %d (per-kernel HIP "
-           "events) launches at most (the last two are capped at 200 and 100).  The routing probe is fused into the partial kernel, so no sr_probe_kernel is dispatched.  sr_read_probe / "
+           "runs slower for its first milliseconds of work), then %d warm-up + 1 queued + %d timed launches, 50 to 200 for the step-time spread and 100 "
+           "with per-kernel HIP events.  The routing probe is fused into the partial kernel, so no sr_probe_kernel is dispatched.  sr_read_probe / "
            "sr_copy_probe are the benchmark's calibration kernels (2 GiB streaming read; 1 GiB copy of known traffic)."
-           % (warmup, steps, steps, steps), "",
+           % (warmup, steps), "",
            "## kernel-trace --stats (durations in us, all dispatches of a kernel name)", "",
            "| kernel | calls | avg | min | max |", "|---|---|---|---|---|"]
     for r in csv.DictReader(open(find(base, "t_kernel_stats.csv"))):
