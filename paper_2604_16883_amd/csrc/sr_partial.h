@@ -360,7 +360,9 @@ __device__ __forceinline__ int wave_inclusive_scan(int x) {
 }
 
 template <bool kFused, bool kPaged>
-__global__ __launch_bounds__(kThreads, 2) void sr_partial_balanced_kernel(PartialArgs a) {
+// (The measurement build's stamps take a few registers more than two workgroups per compute unit leave: it is built for one,
+// which is what the persistent grid runs anyway.)
+__global__ __launch_bounds__(kThreads, SR_TIMELINE ? 1 : 2) void sr_partial_balanced_kernel(PartialArgs a) {
   __shared__ int start[kMaxSchedGroups + 1];
   __shared__ int lens[kMaxSchedGroups];
   __shared__ float cosv[kFused ? kMaxFusedHeads : 1];
