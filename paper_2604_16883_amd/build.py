@@ -23,9 +23,10 @@ HIPCC_FLAGS = [
 ]
 
 
-def build_library(verbose: bool = False, extra=(), timeline: bool = False) -> str:
-    """Compile the library (or, with ``timeline``, its measurement variant) unconditionally; returns its path."""
-    LIB = TIMELINE_LIB if timeline else globals()["LIB"]
+def build_library(verbose: bool = False, extra=(), timeline: bool = False, out: str = "") -> str:
+    """Compile the library (or, with ``timeline``, its measurement variant) unconditionally; returns its path
+    (``out`` if given, else the in-tree location).  Raises if hipcc fails or any kernel spills registers."""
+    LIB = out or (TIMELINE_LIB if timeline else globals()["LIB"])
     extra = list(extra) + (["-DSR_TIMELINE=1"] if timeline else [])
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     tmp = LIB + ".tmp.%d" % os.getpid()

@@ -249,3 +249,17 @@ def test_struct_sizes_match_the_c_compiler(tmp_path):
     P = B.RouteParams
     assert got == [ctypes.sizeof(P), P.tau_coef.offset, P.k0_norm.offset, P.workspace.offset, P.stream.offset,
                    ctypes.sizeof(B.Plan), ctypes.sizeof(B.PagedLayout)]
+
+
+@pytest.mark.parametrize("timeline", [False, True], ids=["product", "measurement"])
+def test_both_library_variants_compile_without_register_spills(tmp_path, timeline):
+    """The build script refuses a library whose kernels spill registers to scratch memory; the measurement variant
+    (wall-clock stamps in the kernels) has its own register budget and must pass as well as the product one."""
+    import shutil
+    from paper_2604_16883_amd import build
+    if not (os.path.exists(os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")) or shutil.which("hipcc")):
+        pytest.skip("no hipcc here")
+    out = build.build_library(timeline=timeline, out=str(tmp_path / "lib.so"))
+    lib = ctypes.CDLL(out)
+    lib.sinkrouter_timeline_bytes.restype = ctypes.c_size_t
+    assert (lib.sinkrouter_timeline_bytes() > 0) == timeline
