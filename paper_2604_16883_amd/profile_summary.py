@@ -149,7 +149,7 @@ def main(argv):
     steps, warmup = line["steps"], line["warmup"]
     cmd = "python3 $R/bench.py --workload %s --lean --steps %d --warmup %d" % (wl, steps, warmup)
     out = ["# rocprofv3 summary: sr_partial_balanced_kernel and sr_combine_kernel, workload %s (%s, bf16)" % (wl, det["description"]), "",
-           "Commands (run from /tmp with TMPDIR=/tmp on the MI355X box, R = repository root, D = $R/gpurun_out/prof_%s):" % wl, "",
+           "Commands (run from /tmp with TMPDIR=/tmp on the MI355X box, R = repository root, D = a scratch directory for the raw output):", "",
            "    rocprofv3 --kernel-trace --stats --output-format csv -d $D/trace -o t -- %s > $D/trace.log" % cmd,
            "    rocprofv3 --pmc FETCH_SIZE --output-format csv -d $D/fetch -o f -- %s > $D/fetch.log" % cmd,
            "    rocprofv3 --pmc WRITE_SIZE --output-format csv -d $D/write -o w -- %s > $D/write.log" % cmd,
