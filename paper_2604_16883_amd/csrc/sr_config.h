@@ -45,7 +45,11 @@ constexpr int kCombinePartsWide = 8, kCombinePartsNarrow = 1;
 constexpr int kCombineRowsWide = 4, kCombineRowsNarrow = 4;
 constexpr int kBalancedGrid = SR_GRID;   // persistent workgroups of the balanced schedule: one per compute unit
 constexpr int kMaxSchedGroups = 2048;  // (sequence, KV group) pairs the balanced schedule scans in LDS
-constexpr int kMaxFusedHeads = 512;    // query heads (all sequences) the balanced kernel probes itself
+// Query heads (all sequences) up to which the balanced kernel probes itself.  Every workgroup evaluates all heads, 128 per
+// sweep, so the cost grows with the batch while a separate probe launch costs a fixed ~4.7 us.  Measured on an 8B-shaped
+// layer (step with the fused / the separate probe): 160 heads 46.9 / 47.6 us, 192: 30.3 / 31.1, 256: 21.9 / 22.6,
+// 320: 42.7 / 42.2, 384: 32.3 / 31.7, 512: 37.4 / 35.9, 640: 44.1 / 41.7, 1024: 69.1 / 64.2.
+constexpr int kMaxFusedHeads = 256;
 constexpr int kMaxGroupsTotal = 65535; // (sequence, KV group) pairs per call: the y extent of the fixed grid
 constexpr int kMaxSeqLen = 1 << 24;    // 32-bit token arithmetic stays exact up to here
 constexpr int64_t kMaxHeadsTotal = (int64_t)1 << 24;

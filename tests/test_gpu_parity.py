@@ -63,20 +63,24 @@ def test_group_sizes(Hq, Hkv):
 
 
 def test_large_batches_take_the_unfused_and_fixed_paths():
-    # more than 512 query heads in the batch: separate probe kernel + balanced schedule
+    # more than 256 query heads in the batch: separate probe kernel + balanced schedule
     w = synth.Workload("wide", 20, 32, 8, 300, 0.6, base_seed=91)
     sb = synth.generate(w, seq_lens=[300 - 7 * b for b in range(20)])
     reps = _check(sb, label="B20 (unfused probe)")
     assert 0 < reps[0]["skip_ratio"] < 1
-    # more than 512 query heads but at most 64 groups: separate probe kernel + schedule built in registers
+    # more than 256 query heads but at most 64 groups: separate probe kernel + schedule built in registers
     w = synth.Workload("wide_groups", 40, 16, 1, 260, 0.6, base_seed=95)
     sb = synth.generate(w, seq_lens=[260 - 6 * b for b in range(40)])
     reps = _check(sb, label="B40 G16 (unfused probe, 40 groups)")
     assert 0 < reps[0]["skip_ratio"] < 1
-    # exactly 512 query heads: the fused probe sweeps four times
-    w = synth.Workload("fused512", 16, 32, 8, 200, 0.6, base_seed=93)
-    sb = synth.generate(w, seq_lens=[200 - 11 * (b % 9) for b in range(16)])
-    reps = _check(sb, label="B16 (fused probe, 512 heads)")
+    # exactly 256 query heads: the fused probe sweeps twice; one head more: the separate probe
+    w = synth.Workload("fused256", 8, 32, 8, 200, 0.6, base_seed=93)
+    sb = synth.generate(w, seq_lens=[200 - 11 * (b % 9) for b in range(8)])
+    reps = _check(sb, label="B8 (fused probe, 256 heads)")
+    assert 0 < reps[0]["skip_ratio"] < 1
+    w = synth.Workload("unfused272", 17, 16, 4, 200, 0.6, base_seed=96)
+    sb = synth.generate(w, seq_lens=[200 - 9 * (b % 11) for b in range(17)])
+    reps = _check(sb, label="B17 (separate probe, 272 heads)")
     assert 0 < reps[0]["skip_ratio"] < 1
     # 2000 (sequence, group) pairs: the schedule scan runs eight rounds
     w = synth.Workload("scan", 250, 16, 8, 100, 0.6, base_seed=94)
