@@ -559,6 +559,32 @@ def results_markdown(line):
     return "\n".join(out) + "\n"
 
 
+BATCH_SWEEP = [(8, 8192, False), (16, 16384, False), (32, 8192, False), (64, 8192, False), (64, 4096, False), (128, 4096, False),
+               (32, 8192, True), (64, 8192, True)]
+
+
+def batch_sweep_markdown(steps, warmup):
+    """Large batches of short contexts (the serving regime; none of the paper's workloads): the 8B-shaped layer (32 query /
+    8 KV heads) with B sequences of L tokens, or of seeded ragged lengths in [0.15 L, L]; routed at tau = 0.55 and dense."""
+    out = ["Large batches on the 8B-shaped layer (32 query / 8 KV heads), routed at tau = 0.55 and dense (routing off); fraction of 8 TB/s "
+           "on the bytes read; `python bench.py --batch-sweep`:", "",
+           "| sequences | context | lengths | groups | active | probe | routed step us | of 8 TB/s | dense step us | of 8 TB/s | speed-up |",
+           "|---|---|---|---|---|---|---|---|---|---|---|"]
+    for B, L, ragged in BATCH_SWEEP:
+        rng = np.random.default_rng(B * 1000 + L)
+        lens = [int(L * f) for f in rng.uniform(0.15, 1.0, B)] if ragged else [L] * B
+        lens[0] = L
+        case = Case("c1", 0, seq_lens=lens)
+        r = case.time_mode(steps, warmup, routing=True, tau=TAU, cached_anchors=False)
+        d = case.time_mode(steps, warmup, routing=False, tau=TAU, cached_anchors=False)
+        out.append("| %d | %d | %s | %d | %d | %s | %.1f | %.1f %% | %.1f | %.1f %% | %.2fx |" % (
+            B, L, "ragged" if ragged else "equal", B * 8, r["active_groups"], "separate launch" if r["probe_us"] else "fused",
+            r["us_per_step"], 100 * r["step_frac_of_peak"], d["us_per_step"], 100 * d["step_frac_of_peak"], d["us_per_step"] / r["us_per_step"]))
+        del case
+        settle()
+    return "\n".join(out)
+
+
 def hbm_calibration(nbytes=2 << 30, reps=10):
     """Achieved streaming-read bandwidth of a plain 128-bit read kernel (context for the roofline)."""
     import torch
@@ -624,6 +650,9 @@ def main():
                          "build (python -m paper_2604_16883_amd.build --timeline); prints markdown")
     ap.add_argument("--prefill-anchors", action="store_true",
                     help="--timeline: route on prefill-cached anchors and norms instead of row 0 of the key cache")
+    ap.add_argument("--batch-sweep", action="store_true",
+                    help="instead of the benchmark: large batches of short contexts on the 8B-shaped layer (equal and ragged "
+                         "lengths), routed and dense; prints a markdown table")
     ap.add_argument("--markdown", default="", metavar="PATH", help="also write the result tables as markdown to PATH")
     ap.add_argument("-v", "--verbose", action="store_true")
     a = ap.parse_args()
@@ -652,6 +681,10 @@ def main():
                 print(timeline_markdown(rep, calib), flush=True)
                 print("<!-- %s -->\n" % json.dumps(rep), flush=True)
                 settle()
+        return
+
+    if a.batch_sweep:
+        print(batch_sweep_markdown(a.steps, a.warmup), flush=True)
         return
 
     main_res, case = run_workload(a.workload, a.steps, a.warmup, a.copies, a.verbose, a.num_splits, a.paged, a.graph)

@@ -127,7 +127,9 @@ int decode_impl(const void* q, const void* k, const void* v, const int32_t* seq_
   PageMap pm = {nullptr, 0, 0, 0};
   if (pages) pm = *pages;
   const bool paged = pm.table != nullptr;
-  const bool fused = balanced && (int64_t)p->batch * p->n_q_heads <= kMaxFusedHeads;
+  // the balanced kernel evaluates the routing rule itself for batches of up to kMaxFusedHeads query heads; with routing off
+  // there is nothing to evaluate (it writes a mask of zeros), so no probe launch precedes it either
+  const bool fused = balanced && ((int64_t)p->batch * p->n_q_heads <= kMaxFusedHeads || !p->routing_enabled);
   // Concentration statistics: the caches are entered one row later with lengths one shorter, so the
   // partial kernels see tokens 1..L-1 (row L-1 is the last one read, as in a plain call).
   const void* k_anchor = k;
