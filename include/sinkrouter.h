@@ -131,8 +131,8 @@ size_t sinkrouter_workspace_bytes(const sr_route_params* params /*host*/);
  *                 Sink Groups and for sequences of length 0
  *   skip_mask_out device uint8 [B,H_kv]: 1 = Sink Group (skipped), 0 = Active Group
  * Enqueued on params->stream: the Split-K partial kernel, which evaluates the routing rule itself
- * (a separate routing-probe kernel precedes it for batches of more than 256 query heads or with
- * fixed chunks), then the merge kernel.  Nothing is allocated, no memset is recorded and nothing
+ * (a separate routing-probe kernel precedes it for routed batches of more than 256 query heads
+ * or with fixed chunks), then the merge kernel.  Nothing is allocated, no memset is recorded and nothing
  * synchronises, so the call can be captured into a HIP graph.
  */
 int sinkrouter_decode(const void* q, const void* k_cache, const void* v_cache,
